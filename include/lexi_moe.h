@@ -1,0 +1,128 @@
+/* lexi_moe.h -- C ABI of the MI355X (gfx950) MoE-layer forward with a per-layer number of active experts.
+ *
+ * The operation (paper Sec. 2, "Mixture of Experts"):
+ *
+ *     y = sum_{i in TopK_k(x)} G(x)_i * E_i(x),      G(x) = Softmax(TopK[x * W_g])
+ *
+ * TopK keeps the k experts with the highest gating scores, Softmax normalises
+ * the kept scores, each expert E_i is a SwiGLU FFN
+ *     E(x) = Wdown * ( silu(Wgate x) .* (Wup x) ).
+ * k is an argument of every call (the UpdateTopk step of Algorithm 1 changes
+ * k and nothing else), and a stack of layers takes the static per-layer
+ * allocation k* = (k_1 .. k_L) that Algorithm 2 outputs.
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers inside lexi_layer_t, x, y, workspace and every field of
+ *     lexi_routing_out_t are DEVICE pointers owned by the caller.  The
+ *     lexi_layer_t / lexi_routing_out_t structs themselves, and k_vec, live in
+ *     HOST memory.  The library never allocates, frees or keeps a pointer.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL
+ *     = the default stream) and the call returns without synchronising.
+ *   - On error a negative lexi_status is returned and nothing is launched.
+ *   - Same inputs give the same output bits on every call; no call leaves
+ *     state behind (k=2 then k=8 gives the k=8 result of a fresh call).
+ *   - Row-major layouts, last index contiguous:
+ *       x, y           [T][d]
+ *       w_router       [d][E]   fp32 always (router runs in fp32)
+ *       router_bias    [E]      fp32, added to the logits before selection, or NULL
+ *       w_gate, w_up   [E][F][d]   one row = the input weights of one hidden feature
+ *       w_down         [E][d][F]   one row = the input weights of one output feature
+ *       ws_gate, ws_up [Fs][d],  ws_down [d][Fs],  w_shared_gate [d]
+ *     dtype LEXI_BF16: x, expert weights and the SwiGLU intermediate are bf16,
+ *     accumulation is fp32.  dtype LEXI_F32: everything fp32.
+ *   - Shape limits: 1 <= E <= 64, d % 128 == 0, F % 64 == 0, F_shared % 64 == 0,
+ *     1 <= k <= E, T >= 0 (T == 0 returns LEXI_OK and launches nothing),
+ *     T * k < 2^24.  Every device pointer must be 16-byte aligned.
+ *   - Routing semantics: selection on the fp32 logits in the total order (logit
+ *     descending, expert index ascending) -- ties go to the lower index, +0 == -0;
+ *     inputs must be finite.  The k selected experts are kept in rank order
+ *     ("slots").  Gates are the softmax over the k selected logits (sum to 1).
+ *     The fp32 logit is evaluated in a fixed order: d is cut into segments of
+ *     128; a segment's partial starts at +0 and takes one fused multiply-add per
+ *     element in ascending order; partials are added in ascending order; the
+ *     bias is added last.
+ *   - Permutation: assignment a = t*k + s (token t, slot s); assignments are
+ *     sorted by (expert, token) into contiguous per-expert groups.
+ */
+#ifndef LEXI_MOE_H
+#define LEXI_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LEXI_OK = 0,
+    LEXI_ERR_NULL = -1,      /* a required pointer is NULL */
+    LEXI_ERR_SHAPE = -2,     /* a dimension violates the shape limits above */
+    LEXI_ERR_BAD_K = -3,     /* k < 1 or k > E */
+    LEXI_ERR_DTYPE = -4,     /* unknown dtype / shared_kind / mode */
+    LEXI_ERR_WORKSPACE = -5, /* workspace_bytes smaller than lexi_moe_workspace_bytes() */
+    LEXI_ERR_ALIGN = -6,     /* a device pointer is not 16-byte aligned */
+    LEXI_ERR_LAUNCH = -7     /* the HIP runtime refused a launch */
+} lexi_status;
+
+typedef enum { LEXI_F32 = 0, LEXI_BF16 = 1 } lexi_dtype;
+typedef enum { LEXI_SHARED_NONE = 0, LEXI_SHARED_UNGATED = 1, LEXI_SHARED_SIGMOID = 2 } lexi_shared_kind;
+
+/* One MoE layer (Sec. 2: gate W_g and experts E_i).  Host struct, device pointers. */
+typedef struct {
+    int32_t d, E, F, F_shared;  /* F_shared = 0: no shared expert (two shared experts = one of twice the width) */
+    int32_t dtype;              /* lexi_dtype of x, expert weights and the SwiGLU intermediate */
+    int32_t shared_kind;        /* lexi_shared_kind */
+    const float* w_router;      /* [d][E] */
+    const float* router_bias;   /* [E] or NULL */
+    const void* w_gate;         /* [E][F][d] */
+    const void* w_up;           /* [E][F][d] */
+    const void* w_down;         /* [E][d][F] */
+    const void* ws_gate;        /* [Fs][d] or NULL */
+    const void* ws_up;          /* [Fs][d] or NULL */
+    const void* ws_down;        /* [d][Fs] or NULL */
+    const void* w_shared_gate;  /* [d] (LEXI_SHARED_SIGMOID) or NULL */
+} lexi_layer_t;
+
+/* Optional routing outputs; any field may be NULL.  Device pointers. */
+typedef struct {
+    int32_t* topk_idx;  /* [T][k]  selected experts in rank order */
+    float* gates;       /* [T][k]  softmax over the selected logits */
+    int32_t* counts;    /* [E]     assignments per expert */
+    int32_t* offsets;   /* [E+1]   exclusive scan of counts */
+    int32_t* perm;      /* [T*k]   position -> assignment t*k+s */
+    int32_t* inv_perm;  /* [T*k]   assignment -> position */
+} lexi_routing_out_t;
+
+/* Bytes of device workspace that any call with these layers, T <= T_max and k <= k_max needs.
+ * layers: host array[L].  Returns 0 if an argument is invalid. */
+size_t lexi_moe_workspace_bytes(const lexi_layer_t* layers, int32_t L, int32_t T_max, int32_t k_max);
+
+/* f_moe(X; k) for one layer (Sec. 2; Algorithm 1's UpdateTopk + f_moe).
+ *   x [T][d] of layer->dtype; y [T][d] of y_dtype (LEXI_F32, or LEXI_BF16 = nearest-even rounding of the fp32 result);
+ *   workspace: device scratch of at least lexi_moe_workspace_bytes(layer, 1, T, k) bytes, contents undefined on
+ *   entry and exit; dbg: NULL or where to copy the routing decision. */
+lexi_status lexi_moe_layer_forward(const lexi_layer_t* layer, const void* x, void* y, int32_t y_dtype, int32_t T,
+                                   int32_t k, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                   const lexi_routing_out_t* dbg);
+
+/* A stack of L layers with the static per-layer allocation k_vec = (k_1 .. k_L) (Sec. 1; output of Algorithm 2).
+ *   layers: host array[L]; k_vec: HOST int32[L].
+ *   mode 0 (the only one): layer l reads x + l*x_layer_stride elements and writes y + l*y_layer_stride elements
+ *   (stride 0 for x = every layer reads the same X, as in Algorithm 1's per-layer profiling on one random X).
+ *   dbg_per_layer: NULL or host array[L]. */
+lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const int32_t* k_vec, const void* x,
+                                   int64_t x_layer_stride, void* y, int64_t y_layer_stride, int32_t y_dtype,
+                                   int32_t T, int32_t mode, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream, const lexi_routing_out_t* dbg_per_layer);
+
+/* Static description of a status code. */
+const char* lexi_strerror(int32_t status);
+
+/* Names of the device kernels one call launches are stable; this returns the library's version string. */
+const char* lexi_moe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LEXI_MOE_H */

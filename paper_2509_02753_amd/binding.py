@@ -1,0 +1,183 @@
+"""ctypes binding of liblexi_moe.so: argument marshalling only, every step of the path runs in the HIP kernels.
+
+PyTorch is used for device memory and streams, nothing else.  If the library has not been built the import of
+this module fails loudly; there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblexi_moe.so")
+
+LEXI_OK = 0
+LEXI_F32, LEXI_BF16 = 0, 1
+SHARED_NONE, SHARED_UNGATED, SHARED_SIGMOID = 0, 1, 2
+
+EXPORTS = ("lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward", "lexi_strerror",
+           "lexi_moe_version")
+
+
+class LexiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class lexi_layer_t(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_int32), ("E", ctypes.c_int32), ("F", ctypes.c_int32), ("F_shared", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("shared_kind", ctypes.c_int32),
+                ("w_router", ctypes.c_void_p), ("router_bias", ctypes.c_void_p),
+                ("w_gate", ctypes.c_void_p), ("w_up", ctypes.c_void_p), ("w_down", ctypes.c_void_p),
+                ("ws_gate", ctypes.c_void_p), ("ws_up", ctypes.c_void_p), ("ws_down", ctypes.c_void_p),
+                ("w_shared_gate", ctypes.c_void_p)]
+
+
+class lexi_routing_out_t(ctypes.Structure):
+    _fields_ = [("topk_idx", ctypes.c_void_p), ("gates", ctypes.c_void_p), ("counts", ctypes.c_void_p),
+                ("offsets", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("inv_perm", ctypes.c_void_p)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_02753_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    lib.lexi_moe_workspace_bytes.restype = sz
+    lib.lexi_moe_workspace_bytes.argtypes = [ctypes.POINTER(lexi_layer_t), i32, i32, i32]
+    lib.lexi_moe_layer_forward.restype = i32
+    lib.lexi_moe_layer_forward.argtypes = [ctypes.POINTER(lexi_layer_t), vp, vp, i32, i32, i32, vp, sz, vp,
+                                           ctypes.POINTER(lexi_routing_out_t)]
+    lib.lexi_moe_stack_forward.restype = i32
+    lib.lexi_moe_stack_forward.argtypes = [ctypes.POINTER(lexi_layer_t), i32, ctypes.POINTER(i32), vp, i64, vp, i64,
+                                           i32, i32, i32, vp, sz, vp, ctypes.POINTER(lexi_routing_out_t)]
+    lib.lexi_strerror.restype = ctypes.c_char_p
+    lib.lexi_strerror.argtypes = [i32]
+    lib.lexi_moe_version.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def strerror(status: int) -> str:
+    return _lib.lexi_strerror(int(status)).decode()
+
+
+def version() -> str:
+    return _lib.lexi_moe_version().decode()
+
+
+def _dp(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return LEXI_F32
+    if t == torch.bfloat16:
+        return LEXI_BF16
+    raise ValueError(f"unsupported dtype {t}")
+
+
+class Layer:
+    """Host-side lexi_layer_t plus references that keep its device tensors alive."""
+
+    def __init__(self, w_router, w_gate, w_up, w_down, router_bias=None, ws_gate=None, ws_up=None, ws_down=None,
+                 w_shared_gate=None, shared_kind: Optional[int] = None):
+        E, F, d = w_gate.shape
+        self.d, self.E, self.F = int(d), int(E), int(F)
+        self.F_shared = 0 if ws_gate is None else int(ws_gate.shape[0])
+        if shared_kind is None:
+            shared_kind = SHARED_NONE if ws_gate is None else (SHARED_SIGMOID if w_shared_gate is not None else SHARED_UNGATED)
+        self.shared_kind = shared_kind
+        self.dtype = w_gate.dtype
+        self.tensors = dict(w_router=w_router, router_bias=router_bias, w_gate=w_gate, w_up=w_up, w_down=w_down,
+                            ws_gate=ws_gate, ws_up=ws_up, ws_down=ws_down, w_shared_gate=w_shared_gate)
+        for name, t in self.tensors.items():
+            if t is not None and not (t.is_cuda and t.is_contiguous()):
+                raise ValueError(f"{name}: contiguous CUDA tensor required")
+        self.c = lexi_layer_t(self.d, self.E, self.F, self.F_shared, _dtype_code(self.dtype), shared_kind,
+                              _dp(w_router), _dp(router_bias), _dp(w_gate), _dp(w_up), _dp(w_down), _dp(ws_gate),
+                              _dp(ws_up), _dp(ws_down), _dp(w_shared_gate))
+
+    @classmethod
+    def from_tensors(cls, tensors: Dict[str, Optional[torch.Tensor]], shared_kind: Optional[int] = None) -> "Layer":
+        return cls(tensors["w_router"], tensors["w_gate"], tensors["w_up"], tensors["w_down"],
+                   router_bias=tensors.get("router_bias"), ws_gate=tensors.get("ws_gate"), ws_up=tensors.get("ws_up"),
+                   ws_down=tensors.get("ws_down"), w_shared_gate=tensors.get("w_shared_gate"), shared_kind=shared_kind)
+
+
+class RoutingOut:
+    """Device arrays that receive the routing decision of one layer call."""
+
+    def __init__(self, T: int, k: int, E: int, device="cuda:0"):
+        i32 = dict(dtype=torch.int32, device=device)
+        self.topk_idx = torch.empty((T, k), **i32)
+        self.gates = torch.empty((T, k), dtype=torch.float32, device=device)
+        self.counts = torch.empty(E, **i32)
+        self.offsets = torch.empty(E + 1, **i32)
+        self.perm = torch.empty(T * k, **i32)
+        self.inv_perm = torch.empty(T * k, **i32)
+        self.c = lexi_routing_out_t(_dp(self.topk_idx), _dp(self.gates), _dp(self.counts), _dp(self.offsets),
+                                    _dp(self.perm), _dp(self.inv_perm))
+
+
+def _layer_array(layers: Sequence[Layer]):
+    arr = (lexi_layer_t * len(layers))()
+    for i, ly in enumerate(layers):
+        arr[i] = ly.c
+    return arr
+
+
+def lexi_moe_workspace_bytes(layers: Sequence[Layer], T_max: int, k_max: int) -> int:
+    return int(_lib.lexi_moe_workspace_bytes(_layer_array(layers), len(layers), T_max, k_max))
+
+
+def alloc_workspace(layers: Sequence[Layer], T_max: int, k_max: int, device="cuda:0") -> torch.Tensor:
+    n = lexi_moe_workspace_bytes(layers, T_max, k_max)
+    if n == 0:
+        raise LexiError(-2, "lexi_moe_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def lexi_moe_layer_forward(layer: Layer, x: torch.Tensor, y: torch.Tensor, k: int, workspace: torch.Tensor,
+                           routing: Optional[RoutingOut] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """y = f_moe(x; k) for one layer, enqueued on `stream` (default: torch's current stream)."""
+    T = int(x.shape[0])
+    st = _lib.lexi_moe_layer_forward(ctypes.byref(layer.c), _dp(x), _dp(y), _dtype_code(y.dtype), T, int(k),
+                                     _dp(workspace), workspace.numel(), _stream_ptr(stream),
+                                     ctypes.byref(routing.c) if routing is not None else None)
+    if st != LEXI_OK:
+        raise LexiError(st, "lexi_moe_layer_forward")
+
+
+def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: torch.Tensor, y: torch.Tensor,
+                           workspace: torch.Tensor, routing: Optional[Sequence[RoutingOut]] = None,
+                           stream: Optional[torch.cuda.Stream] = None, layer_array=None) -> None:
+    """Stack of L layers with the per-layer k vector.  x: [T][d] (shared by all layers) or [L][T][d]; y: [L][T][d]."""
+    L = len(layers)
+    T = int(x.shape[-2])
+    x_stride = 0 if x.dim() == 2 else int(x.stride(0))
+    y_stride = int(y.stride(0)) if y.dim() == 3 else 0
+    kv = (ctypes.c_int32 * L)(*[int(v) for v in k_vec])
+    dbg = None
+    if routing is not None:
+        dbg = (lexi_routing_out_t * L)()
+        for i, r in enumerate(routing):
+            dbg[i] = r.c
+    arr = layer_array if layer_array is not None else _layer_array(layers)
+    st = _lib.lexi_moe_stack_forward(arr, L, kv, _dp(x), x_stride, _dp(y), y_stride, _dtype_code(y.dtype), T, 0,
+                                     _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg)
+    if st != LEXI_OK:
+        raise LexiError(st, "lexi_moe_stack_forward")

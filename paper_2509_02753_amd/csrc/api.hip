@@ -1,0 +1,237 @@
+// C ABI of the library: argument validation, workspace slicing and the per-layer launch sequence.
+// Nothing here allocates, synchronises or copies to the host; every launch goes to the caller's stream.
+#include "../../include/lexi_moe.h"
+#include "kernels.hpp"
+
+namespace {
+
+using namespace lexi;
+
+constexpr int kTileTokens = 128;  // token-tile height of the grouped GEMM kernels
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Walks the workspace once; with base == nullptr it only measures.
+struct Carver {
+    char* base;
+    size_t used = 0;
+    explicit Carver(void* b) : base((char*)b) {}
+    template <typename T>
+    T* take(size_t count) {
+        used = align_up(used, 256);
+        T* p = base ? (T*)(base + used) : nullptr;
+        used += count * sizeof(T);
+        return p;
+    }
+};
+
+struct Workspace {
+    int32_t *topk_idx, *local_rank, *blk_hist, *counts, *offsets, *perm, *inv_perm, *row_token, *sched, *sched_count;
+    float *gates, *y_slot, *y_shared, *coef;
+    void *act, *act_shared;
+    int max_tiles;
+    size_t bytes;
+};
+
+Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
+    Workspace w{};
+    Carver c(base);
+    const size_t A = (size_t)T * k;
+    const size_t es = ly.dtype == LEXI_BF16 ? 2 : 4;
+    const size_t nblk = ((size_t)T + 7) / 8;  // router blocks never hold fewer than 8 tokens
+    w.max_tiles = (int)((A + kTileTokens - 1) / kTileTokens) + ly.E;
+    w.topk_idx = c.take<int32_t>(A);
+    w.gates = c.take<float>(A);
+    w.local_rank = c.take<int32_t>(A);
+    w.blk_hist = c.take<int32_t>(nblk * 64);
+    w.counts = c.take<int32_t>(64);
+    w.offsets = c.take<int32_t>(68);
+    w.perm = c.take<int32_t>(A);
+    w.inv_perm = c.take<int32_t>(A);
+    w.row_token = c.take<int32_t>(A);
+    w.sched = c.take<int32_t>((size_t)w.max_tiles * 4);
+    w.sched_count = c.take<int32_t>(4);
+    w.act = c.take<char>(A * ly.F * es);
+    w.y_slot = c.take<float>(A * ly.d);
+    if (ly.F_shared > 0) {
+        w.act_shared = c.take<char>((size_t)T * ly.F_shared * es);
+        w.y_shared = c.take<float>((size_t)T * ly.d);
+        w.coef = c.take<float>((size_t)T);
+    }
+    w.bytes = align_up(c.used, 256);
+    return w;
+}
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+lexi_status check_layer(const lexi_layer_t* ly) {
+    if (ly == nullptr) return LEXI_ERR_NULL;
+    if (ly->dtype != LEXI_F32 && ly->dtype != LEXI_BF16) return LEXI_ERR_DTYPE;
+    if (ly->shared_kind < LEXI_SHARED_NONE || ly->shared_kind > LEXI_SHARED_SIGMOID) return LEXI_ERR_DTYPE;
+    if (ly->E < 1 || ly->E > 64) return LEXI_ERR_SHAPE;
+    if (ly->d < 128 || ly->d % 128 != 0) return LEXI_ERR_SHAPE;
+    if (ly->F < 64 || ly->F % 64 != 0) return LEXI_ERR_SHAPE;
+    if (ly->F_shared < 0 || ly->F_shared % 64 != 0) return LEXI_ERR_SHAPE;
+    if ((ly->F_shared > 0) != (ly->shared_kind != LEXI_SHARED_NONE)) return LEXI_ERR_SHAPE;
+    if (!ly->w_router || !ly->w_gate || !ly->w_up || !ly->w_down) return LEXI_ERR_NULL;
+    if (ly->F_shared > 0 && (!ly->ws_gate || !ly->ws_up || !ly->ws_down)) return LEXI_ERR_NULL;
+    if (ly->shared_kind == LEXI_SHARED_SIGMOID && !ly->w_shared_gate) return LEXI_ERR_NULL;
+    const void* ptrs[] = {ly->w_router, ly->router_bias, ly->w_gate, ly->w_up, ly->w_down,
+                          ly->ws_gate, ly->ws_up, ly->ws_down, ly->w_shared_gate};
+    for (const void* p : ptrs)
+        if (p && misaligned(p)) return LEXI_ERR_ALIGN;
+    return LEXI_OK;
+}
+
+lexi_status check_call(const lexi_layer_t* ly, const void* x, const void* y, int32_t y_dtype, int32_t T, int32_t k,
+                       const void* workspace, size_t workspace_bytes, const lexi_routing_out_t* dbg) {
+    lexi_status st = check_layer(ly);
+    if (st != LEXI_OK) return st;
+    if (y_dtype != LEXI_F32 && y_dtype != LEXI_BF16) return LEXI_ERR_DTYPE;
+    if (T < 0) return LEXI_ERR_SHAPE;
+    if (k < 1 || k > ly->E) return LEXI_ERR_BAD_K;
+    if ((int64_t)T * k >= (1 << 24)) return LEXI_ERR_SHAPE;
+    if (T == 0) return LEXI_OK;
+    if (!x || !y || !workspace) return LEXI_ERR_NULL;
+    if (misaligned(x) || misaligned(y) || misaligned(workspace)) return LEXI_ERR_ALIGN;
+    if (dbg) {
+        const void* ptrs[] = {dbg->topk_idx, dbg->gates, dbg->counts, dbg->offsets, dbg->perm, dbg->inv_perm};
+        for (const void* p : ptrs)
+            if (p && misaligned(p)) return LEXI_ERR_ALIGN;
+    }
+    if (workspace_bytes < carve(*ly, T, k, nullptr).bytes) return LEXI_ERR_WORKSPACE;
+    return LEXI_OK;
+}
+
+// One layer, arguments already validated.
+lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_dtype, int32_t T, int32_t k,
+                      void* workspace, hipStream_t s, const lexi_routing_out_t* dbg) {
+    Workspace w = carve(ly, T, k, workspace);
+    const bool bf = ly.dtype == LEXI_BF16;
+    // routing results land directly in the caller's arrays when those are given
+    if (dbg) {
+        if (dbg->topk_idx) w.topk_idx = dbg->topk_idx;
+        if (dbg->gates) w.gates = dbg->gates;
+        if (dbg->counts) w.counts = dbg->counts;
+        if (dbg->offsets) w.offsets = dbg->offsets;
+        if (dbg->perm) w.perm = dbg->perm;
+        if (dbg->inv_perm) w.inv_perm = dbg->inv_perm;
+    }
+
+    RoutingArgs r{};
+    r.x = x; r.is_bf16 = bf; r.w_router = ly.w_router; r.bias = ly.router_bias;
+    r.T = T; r.d = ly.d; r.E = ly.E; r.k = k; r.tile_tokens = kTileTokens;
+    r.topk_idx = w.topk_idx; r.gates = w.gates; r.local_rank = w.local_rank; r.blk_hist = w.blk_hist;
+    r.counts = w.counts; r.offsets = w.offsets; r.perm = w.perm; r.inv_perm = w.inv_perm; r.row_token = w.row_token;
+    r.sched = w.sched; r.sched_count = w.sched_count;
+    if (launch_routing(r, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+
+    FfnArgs g{};
+    g.is_bf16 = bf; g.in = x; g.row_token = w.row_token; g.w0 = ly.w_gate; g.w1 = ly.w_up; g.K = ly.d;
+    g.features = ly.F; g.M = T * k; g.max_tiles = w.max_tiles; g.tile_tokens = kTileTokens; g.sched = w.sched;
+    g.sched_count = w.sched_count; g.out = w.act;
+    if (launch_gateup(g, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+
+    FfnArgs dn{};
+    dn.is_bf16 = bf; dn.in = w.act; dn.row_token = nullptr; dn.w0 = ly.w_down; dn.w1 = nullptr; dn.K = ly.F;
+    dn.features = ly.d; dn.M = T * k; dn.max_tiles = w.max_tiles; dn.tile_tokens = kTileTokens; dn.sched = w.sched;
+    dn.sched_count = w.sched_count; dn.out = w.y_slot;
+    if (launch_down(dn, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+
+    if (ly.F_shared > 0) {
+        const int dense_tiles = (T + kTileTokens - 1) / kTileTokens;
+        FfnArgs sg{};
+        sg.is_bf16 = bf; sg.in = x; sg.row_token = nullptr; sg.w0 = ly.ws_gate; sg.w1 = ly.ws_up; sg.K = ly.d;
+        sg.features = ly.F_shared; sg.M = T; sg.max_tiles = dense_tiles; sg.tile_tokens = kTileTokens;
+        sg.sched = nullptr; sg.sched_count = nullptr; sg.out = w.act_shared;
+        if (launch_gateup(sg, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+        FfnArgs sd{};
+        sd.is_bf16 = bf; sd.in = w.act_shared; sd.row_token = nullptr; sd.w0 = ly.ws_down; sd.w1 = nullptr;
+        sd.K = ly.F_shared; sd.features = ly.d; sd.M = T; sd.max_tiles = dense_tiles; sd.tile_tokens = kTileTokens;
+        sd.sched = nullptr; sd.sched_count = nullptr; sd.out = w.y_shared;
+        if (launch_down(sd, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+        if (ly.shared_kind == LEXI_SHARED_SIGMOID &&
+            launch_shared_gate(x, ly.w_shared_gate, bf, T, ly.d, w.coef, s) != hipSuccess)
+            return LEXI_ERR_LAUNCH;
+    }
+
+    CombineArgs c{};
+    c.y_slot = w.y_slot; c.inv_perm = w.inv_perm; c.gates = w.gates;
+    c.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr;
+    c.shared_coef = ly.shared_kind == LEXI_SHARED_SIGMOID ? w.coef : nullptr;
+    c.T = T; c.d = ly.d; c.k = k; c.y = y; c.y_bf16 = y_dtype == LEXI_BF16;
+    if (launch_combine(c, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+    return LEXI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lexi_moe_workspace_bytes(const lexi_layer_t* layers, int32_t L, int32_t T_max, int32_t k_max) {
+    if (!layers || L < 1 || T_max < 0 || k_max < 1) return 0;
+    size_t need = 256;
+    for (int l = 0; l < L; ++l) {
+        if (check_layer(&layers[l]) != LEXI_OK || k_max > layers[l].E) return 0;
+        const size_t b = carve(layers[l], T_max, k_max, nullptr).bytes;
+        need = b > need ? b : need;
+    }
+    return need;
+}
+
+lexi_status lexi_moe_layer_forward(const lexi_layer_t* layer, const void* x, void* y, int32_t y_dtype, int32_t T,
+                                   int32_t k, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                   const lexi_routing_out_t* dbg) {
+    lexi_status st = check_call(layer, x, y, y_dtype, T, k, workspace, workspace_bytes, dbg);
+    if (st != LEXI_OK || T == 0) return st;
+    return run_layer(*layer, x, y, y_dtype, T, k, workspace, (hipStream_t)hip_stream, dbg);
+}
+
+lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const int32_t* k_vec, const void* x,
+                                   int64_t x_layer_stride, void* y, int64_t y_layer_stride, int32_t y_dtype,
+                                   int32_t T, int32_t mode, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream, const lexi_routing_out_t* dbg_per_layer) {
+    if (!layers || !k_vec) return LEXI_ERR_NULL;
+    if (L < 1 || x_layer_stride < 0 || y_layer_stride < 0) return LEXI_ERR_SHAPE;
+    if (mode != 0) return LEXI_ERR_DTYPE;
+    // validate every layer before the first launch: an error must leave nothing enqueued
+    for (int l = 0; l < L; ++l) {
+        const size_t xes = layers[l].dtype == LEXI_BF16 ? 2 : 4;
+        const size_t yes = y_dtype == LEXI_BF16 ? 2 : 4;
+        const void* xl = x ? (const char*)x + (size_t)l * x_layer_stride * xes : nullptr;
+        const void* yl = y ? (const char*)y + (size_t)l * y_layer_stride * yes : nullptr;
+        lexi_status st = check_call(&layers[l], xl, yl, y_dtype, T, k_vec[l], workspace, workspace_bytes,
+                                    dbg_per_layer ? &dbg_per_layer[l] : nullptr);
+        if (st != LEXI_OK) return st;
+        if (L > 1 && T > 0 && y_layer_stride < (int64_t)T * layers[l].d) return LEXI_ERR_SHAPE;  // outputs would overlap
+    }
+    if (T == 0) return LEXI_OK;
+    for (int l = 0; l < L; ++l) {
+        const size_t xes = layers[l].dtype == LEXI_BF16 ? 2 : 4;
+        const size_t yes = y_dtype == LEXI_BF16 ? 2 : 4;
+        const void* xl = (const char*)x + (size_t)l * x_layer_stride * xes;
+        void* yl = (char*)y + (size_t)l * y_layer_stride * yes;
+        lexi_status st = run_layer(layers[l], xl, yl, y_dtype, T, k_vec[l], workspace, (hipStream_t)hip_stream,
+                                   dbg_per_layer ? &dbg_per_layer[l] : nullptr);
+        if (st != LEXI_OK) return st;
+    }
+    return LEXI_OK;
+}
+
+const char* lexi_strerror(int32_t status) {
+    switch (status) {
+        case LEXI_OK: return "ok";
+        case LEXI_ERR_NULL: return "a required pointer is NULL";
+        case LEXI_ERR_SHAPE: return "a dimension violates the shape limits";
+        case LEXI_ERR_BAD_K: return "k outside 1..E";
+        case LEXI_ERR_DTYPE: return "unknown dtype, shared_kind or mode";
+        case LEXI_ERR_WORKSPACE: return "workspace too small";
+        case LEXI_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
+        case LEXI_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+        default: return "unknown status";
+    }
+}
+
+const char* lexi_moe_version(void) { return "lexi-moe gfx950 0.1"; }
+
+}  // extern "C"

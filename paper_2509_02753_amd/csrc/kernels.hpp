@@ -1,0 +1,69 @@
+// Internal launch interface between the C ABI (api.hip) and the kernel translation units.
+#pragma once
+#include "common.hpp"
+
+namespace lexi {
+
+struct RoutingArgs {
+    const void* x;            // [T][d]
+    bool is_bf16;
+    const float* w_router;    // [d][E]
+    const float* bias;        // [E] or null
+    int T, d, E, k;
+    int tile_tokens;          // token-tile height the grouped GEMM schedule is built for
+    int32_t* topk_idx;        // [T*k]
+    float* gates;             // [T*k]
+    int32_t* local_rank;      // [T*k]  rank of the assignment inside its router block, per expert
+    int32_t* blk_hist;        // [nblk][64] histogram, turned into per-expert block prefixes by the scan
+    int32_t* counts;          // [E]
+    int32_t* offsets;         // [E+1]
+    int32_t* perm;            // [T*k]
+    int32_t* inv_perm;        // [T*k]
+    int32_t* row_token;       // [T*k]  permuted row -> token
+    int32_t* sched;           // [max_tiles][4]  (expert, first row, rows, 0)
+    int32_t* sched_count;     // [1]
+};
+
+int router_tokens_per_block(int T);
+hipError_t launch_routing(const RoutingArgs& a, hipStream_t s);
+
+// One grouped (or dense) GEMM of the expert FFN.
+//   GATE/UP:  act[r][f] = silu(in[tok(r)] . Wg[e][f]) * (in[tok(r)] . Wu[e][f])      K = d, features = F
+//   DOWN:     out[r][j] = act[r] . Wd[e][j]                                           K = F, features = d
+// rows r are the permuted assignment rows (grouped: tile schedule from the scan) or plain token rows (dense, sched
+// == null: one group of M rows, expert 0).
+struct FfnArgs {
+    bool is_bf16;
+    const void* in;            // row-major [*][K]
+    const int32_t* row_token;  // gather map row -> input row, or null (identity)
+    const void* w0;            // gate (GATE/UP) or down weights, [E][features][K]
+    const void* w1;            // up weights or null
+    int K;                     // reduction length
+    int features;              // F (gate/up) or d (down)
+    int M;                     // total rows (dense mode bound / grid sizing)
+    int max_tiles;             // upper bound on the number of token tiles
+    int tile_tokens;           // must equal the value the schedule was built with
+    const int32_t* sched;      // null = dense
+    const int32_t* sched_count;
+    void* out;                 // GATE/UP: act [rows][F] (layer dtype);  DOWN: [rows][d] fp32
+};
+
+hipError_t launch_gateup(const FfnArgs& a, hipStream_t s);
+hipError_t launch_down(const FfnArgs& a, hipStream_t s);
+
+struct CombineArgs {
+    const float* y_slot;       // [T*k][d] fp32, permuted rows
+    const int32_t* inv_perm;   // [T*k]
+    const float* gates;        // [T*k]
+    const float* y_shared;     // [T][d] fp32 or null
+    const float* shared_coef;  // [T] or null (= 1)
+    int T, d, k;
+    void* y;                   // [T][d]
+    bool y_bf16;
+};
+hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+
+// coef[t] = sigmoid(x[t] . w)   (the gate in front of a sigmoid-gated shared expert)
+hipError_t launch_shared_gate(const void* x, const void* w, bool is_bf16, int T, int d, float* coef, hipStream_t s);
+
+}  // namespace lexi

@@ -1,0 +1,92 @@
+"""The C-ABI library: loads, exports every declared symbol, and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lexi_moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lexi_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2509_02753_amd as P
+    names = declared_functions()
+    assert set(names) == set(P.EXPORTS)
+    lib = ctypes.CDLL(P.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert P.version().startswith("lexi-moe")
+    assert P.strerror(0) == "ok" and "k" in P.strerror(-3)
+
+
+def fake_layer(P, **over):
+    """A lexi_layer_t with plausible shapes and fake (never dereferenced) aligned device addresses."""
+    f = dict(d=256, E=8, F=128, F_shared=0, dtype=P.LEXI_BF16, shared_kind=0, w_router=0x10000, router_bias=None,
+             w_gate=0x20000, w_up=0x30000, w_down=0x40000, ws_gate=None, ws_up=None, ws_down=None, w_shared_gate=None)
+    f.update(over)
+    from paper_2509_02753_amd.binding import lexi_layer_t
+    return lexi_layer_t(*[f[n] for n, _ in lexi_layer_t._fields_])
+
+
+def call_layer(P, ly, x=0x50000, y=0x60000, y_dtype=0, T=16, k=2, ws=0x70000, ws_bytes=1 << 40):
+    from paper_2509_02753_amd.binding import _lib
+    return _lib.lexi_moe_layer_forward(ctypes.byref(ly), x, y, y_dtype, T, k, ws, ws_bytes, None, None)
+
+
+def test_argument_validation_returns_codes_without_launching():
+    """Every case fails validation (or is T == 0), so no kernel is launched and no GPU is needed."""
+    import paper_2509_02753_amd as P
+    ok = fake_layer(P)
+    assert call_layer(P, ok, T=0) == 0                                   # T = 0: nothing to do
+    assert call_layer(P, ok, k=0) == -3 and call_layer(P, ok, k=9) == -3 and call_layer(P, ok, k=-1) == -3
+    assert call_layer(P, ok, T=-1) == -2
+    assert call_layer(P, ok, x=None) == -1 and call_layer(P, ok, y=None) == -1 and call_layer(P, ok, ws=None) == -1
+    assert call_layer(P, ok, x=0x50004) == -6 and call_layer(P, ok, ws=0x70008) == -6
+    assert call_layer(P, ok, y_dtype=7) == -4
+    assert call_layer(P, ok, ws_bytes=1024) == -5
+    assert call_layer(P, fake_layer(P, E=65)) == -2 and call_layer(P, fake_layer(P, E=0)) == -2
+    assert call_layer(P, fake_layer(P, d=192)) == -2 and call_layer(P, fake_layer(P, F=100)) == -2
+    assert call_layer(P, fake_layer(P, dtype=3)) == -4
+    assert call_layer(P, fake_layer(P, w_gate=None)) == -1
+    assert call_layer(P, fake_layer(P, w_up=0x30002)) == -6
+    assert call_layer(P, fake_layer(P, F_shared=128, shared_kind=1)) == -1          # shared weights missing
+    assert call_layer(P, fake_layer(P, F_shared=128, shared_kind=0)) == -2          # width without a kind
+    assert call_layer(P, fake_layer(P, F_shared=128, shared_kind=2, ws_gate=0x80000, ws_up=0x90000,
+                                    ws_down=0xA0000)) == -1                         # sigmoid gate vector missing
+    assert call_layer(P, ok, T=1 << 23, k=2) == -2                                  # T*k >= 2^24
+
+
+def test_workspace_query_is_monotone_and_checked():
+    import paper_2509_02753_amd as P
+    from paper_2509_02753_amd.binding import _lib, lexi_layer_t
+    arr = (lexi_layer_t * 2)(fake_layer(P), fake_layer(P, F=256, F_shared=128, shared_kind=1, ws_gate=0x80000,
+                                                       ws_up=0x90000, ws_down=0xA0000))
+    q = lambda T, k: int(_lib.lexi_moe_workspace_bytes(arr, 2, T, k))
+    assert q(64, 2) > 0 and q(128, 2) > q(64, 2) and q(64, 4) > q(64, 2)
+    assert q(64, 9) == 0 and q(-1, 2) == 0 and q(64, 0) == 0
+    assert int(_lib.lexi_moe_workspace_bytes(None, 1, 64, 2)) == 0
+    # a stack call validates every layer before launching: bad k in the second layer is reported, nothing runs
+    kv = (ctypes.c_int32 * 2)(2, 0)
+    st = _lib.lexi_moe_stack_forward(arr, 2, kv, 0x50000, 0, 0x60000, 64 * 256, 0, 64, 0, 0x70000, 1 << 40, None, None)
+    assert st == -3
+    kv = (ctypes.c_int32 * 2)(2, 2)
+    assert _lib.lexi_moe_stack_forward(arr, 2, kv, 0x50000, 0, 0x60000, 64 * 256, 0, 64, 1, 0x70000, 1 << 40, None, None) == -4
+    assert _lib.lexi_moe_stack_forward(arr, 2, kv, 0x50000, 0, 0x60000, 10, 0, 64, 0, 0x70000, 1 << 40, None, None) == -2
+    assert _lib.lexi_moe_stack_forward(arr, 2, None, 0x50000, 0, 0x60000, 64 * 256, 0, 64, 0, 0x70000, 1 << 40, None, None) == -1
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2509_02753_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in src.lower(), f"{fn} mentions the oracle"
+    src = open(os.path.join(ROOT, "oracle", "__init__.py")).read() + open(os.path.join(ROOT, "oracle", "lexi_oracle.c")).read()
+    assert "paper_2509_02753_amd" not in src and "lexi_moe.h" not in src
