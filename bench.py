@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""MoE-stack throughput on one MI355X: tokens/s of lexi_moe_stack_forward with a per-layer k vector.
+
+A step is one pass of the whole hot path (router, top-k, gates, permutation, grouped gate/up GEMM + SwiGLU, down
+GEMM, shared expert, combine) over all L layers of the workload, on synthetic seeded inputs already resident in HBM.
+Default workload: the OLMoE-shaped 16-layer stack, T = 4096 prefill tokens, LExI-style k vector (mean 6).
+
+Prints ONE JSON line on stdout; progress and the per-stage table go to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def stage_flops_bytes(cfg, T, kvec, counts_per_layer):
+    """Algorithmic work of the routed gate/up launch and of the whole stack (only selected experts, only touched weights)."""
+    es = 4 if cfg.dtype == "f32" else 2
+    gateup_flops = sum(4.0 * T * int(k) * cfg.d * cfg.F for k in kvec)
+    total_flops = sum(T * (2.0 * cfg.d * cfg.E + int(k) * 6.0 * cfg.d * cfg.F + 6.0 * cfg.d * cfg.F_shared) for k in kvec)
+    total_bytes = 0.0
+    gateup_bytes = 0.0
+    for l, k in enumerate(kvec):
+        U = int((counts_per_layer[l] > 0).sum())
+        total_bytes += U * 3 * cfg.d * cfg.F * es + 3 * cfg.d * cfg.F_shared * es + cfg.d * cfg.E * 4 + T * cfg.d * es + T * cfg.d * 4
+        gateup_bytes += U * 2 * cfg.d * cfg.F * es + T * cfg.d * es
+    return gateup_flops, gateup_bytes, total_flops, total_bytes
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2_olmoe")
+    ap.add_argument("--T", type=int, default=None, help="tokens per step (default: the workload's first regime)")
+    ap.add_argument("--kvec", default="lexi", choices=["lexi", "uniform"])
+    ap.add_argument("--layers", type=int, default=None, help="use only the first N layers (debugging; not a valid result)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+
+    import lexi_synth as S
+    import paper_2509_02753_amd as P
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = S.CONFIGS[args.config]
+    T = args.T if args.T is not None else cfg.T_regimes[0]
+    L = args.layers if args.layers else cfg.L
+    kvec = (cfg.k_lexi() if args.kvec == "lexi" else cfg.k_uniform())[:L]
+    kuni = cfg.k_uniform()[:L]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    log(f"[bench] {cfg.name} T={T} L={L} kvec={kvec.tolist()} (sum {int(kvec.sum())}, uniform {int(kuni.sum())})")
+    t0 = time.time()
+    dev_tensors = [S.device_layer(cfg, l, dev) for l in range(L)]
+    layers = [P.Layer.from_tensors(t, shared_kind=cfg.shared_kind) for t in dev_tensors]
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    x = torch.empty((L, T, cfg.d), dtype=tdt, device=dev)
+    for l in range(L):
+        S.fill_device(x[l], cfg.seed, S.tensor_id(l, S.KIND_X), cfg.sigma_x)
+    y = torch.empty((L, T, cfg.d), dtype=torch.float32, device=dev)
+    ws = P.alloc_workspace(layers, T, int(max(kvec.max(), kuni.max())))
+    torch.cuda.synchronize()
+    log(f"[bench] inputs resident in HBM after {time.time() - t0:.1f}s: weights {cfg.weight_bytes() * L / cfg.L / 1e9:.2f} GB, "
+        f"workspace {ws.numel() / 1e6:.0f} MB")
+
+    from paper_2509_02753_amd.binding import _layer_array
+    arr = _layer_array(layers)
+
+    def run_steps(kv, n, events=None):
+        for _ in range(n):
+            P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr, stage_events=events)
+
+    def timed(kv):
+        run_steps(kv, args.warmup)
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        run_steps(kv, args.steps)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t_start) / args.steps
+
+    sec = timed(kvec)
+    log(f"[bench] k={args.kvec}: {sec * 1e3:.3f} ms/step, {T / sec:,.0f} tokens/s")
+    sec_uniform = timed(kuni) if args.kvec == "lexi" else sec
+    if args.kvec == "lexi":
+        log(f"[bench] uniform k={cfg.k_base}: {sec_uniform * 1e3:.3f} ms/step, {T / sec_uniform:,.0f} tokens/s")
+
+    # ---- per-stage durations with HIP events recorded by the library on the launch stream ----
+    ev = P.StageEvents(L)
+    stage_sum = np.zeros((L, 5))
+    for _ in range(args.steps):
+        run_steps(kvec, 1, events=ev)
+        torch.cuda.synchronize()
+        stage_sum += np.asarray(ev.stage_ms())
+    stage_ms = stage_sum / args.steps            # [L][5] average ms per launch group
+    per_stage = stage_ms.sum(0)
+    log("[bench] stage ms per step: " + ", ".join(f"{n}={v:.3f}" for n, v in zip(P.STAGE_NAMES, per_stage)) +
+        f"  (sum {per_stage.sum():.3f} vs step {sec * 1e3:.3f})")
+
+    # experts touched per layer (for the algorithmic byte count)
+    routs = [P.RoutingOut(T, int(kvec[l]), cfg.E) for l in range(L)]
+    P.lexi_moe_stack_forward(layers, kvec, x, y, ws, routing=routs)
+    torch.cuda.synchronize()
+    counts = [r.counts.cpu().numpy() for r in routs]
+    gu_flops, gu_bytes, tot_flops, tot_bytes = stage_flops_bytes(cfg, T, kvec, counts)
+
+    gu_ms_avg = float(stage_ms[:, 1].mean())      # average duration of one gate/up launch
+    prefill = (T * float(np.mean(kvec)) / cfg.E) >= 64
+    if prefill:
+        achieved = gu_flops / L / (gu_ms_avg * 1e-3) / 1e12
+        roofline = {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "mfma", "achieved": round(achieved, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": None, "avg_launch_ms": round(gu_ms_avg, 4),
+                    "flops_per_launch": gu_flops / L}
+    else:
+        achieved = gu_bytes / L / (gu_ms_avg * 1e-3) / 1e9
+        roofline = {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "hbm", "achieved": round(achieved, 1),
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
+                    "traffic": None, "avg_launch_ms": round(gu_ms_avg, 4),
+                    "bytes_per_launch": gu_bytes / L}
+    whole = {"flops_per_step": tot_flops, "bytes_per_step": tot_bytes,
+             "mfma_frac": round(tot_flops / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
+             "hbm_frac": round(tot_bytes / sec / 1e9 / PEAK_HBM_GBS, 4)}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as O
+        n = args.cpu_sample_tokens or max(1, min(T, int(64 * (6 * 2048 * 1024 * 6) / (float(np.mean(kvec)) * 6 * cfg.d * cfg.F + 6 * cfg.d * cfg.F_shared))))
+
+        def to_host_layer(tensors):
+            """Device tensors of one layer -> numpy (bf16 as uint16 bit patterns); the inputs, copied D2H."""
+            h = {}
+            for name, t in tensors.items():
+                if t is None:
+                    h[name] = None
+                elif t.dtype == torch.bfloat16:
+                    h[name] = t.view(torch.int16).cpu().numpy().view(np.uint16)
+                else:
+                    h[name] = t.cpu().numpy()
+            return h
+
+        wall = 0.0
+        for l in range(L):
+            hl = O.Layer.from_tensors(cfg, to_host_layer(dev_tensors[l]))
+            xh = x[l, :n].contiguous()
+            xh = xh.view(torch.int16).cpu().numpy().view(np.uint16) if tdt == torch.bfloat16 else xh.cpu().numpy()
+            t1 = time.perf_counter()
+            O.moe_layer(hl, xh, int(kvec[l]), round_act=True)
+            wall += time.perf_counter() - t1
+            del hl
+        cpu = {"value": round(n / wall, 3), "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+               "sample": f"first {n} tokens of every layer's input through all {L} layers (router + FFN + combine, fp64), {wall:.1f}s"}
+        log(f"[bench] cpu oracle: {n} tokens x {L} layers in {wall:.1f}s on {O.num_threads()} threads -> {n / wall:.2f} tokens/s")
+
+    out = {
+        "metric": "MoE-stack tokens/s", "value": round(T / sec, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name} L={L} d={cfg.d} E={cfg.E} F={cfg.F} Fs={cfg.F_shared} T={T}",
+                   "k_vec": kvec.tolist(), "k_sum": int(kvec.sum()), "k_uniform": int(cfg.k_base),
+                   "regime": "prefill" if prefill else "decode"},
+        "uniform_k_tokens_per_s": round(T / sec_uniform, 1),
+        "speedup_vs_uniform_k": round(sec_uniform / sec, 4),
+        "stage_ms_per_step": {n: round(float(v), 4) for n, v in zip(P.STAGE_NAMES, per_stage)},
+        "roofline": roofline, "whole_path": whole, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

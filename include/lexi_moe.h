@@ -116,6 +116,24 @@ lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const 
                                    int32_t T, int32_t mode, void* workspace, size_t workspace_bytes,
                                    void* hip_stream, const lexi_routing_out_t* dbg_per_layer);
 
+/* Stage boundaries of one layer, for timing from outside with HIP events: the library records ev[i] on the
+ * stream at boundary i.  0 = layer start, 1 = routing done (router, top-k, gates, permutation), 2 = routed gate/up
+ * GEMM + SwiGLU done, 3 = routed down GEMM done, 4 = shared expert done, 5 = combine done.  A NULL event is
+ * skipped.  Events are hipEvent_t handles owned by the caller (host struct). */
+#define LEXI_N_STAGE_EVENTS 6
+typedef struct {
+    void* ev[LEXI_N_STAGE_EVENTS];
+} lexi_stage_events_t;
+
+/* lexi_moe_stack_forward plus stage events: events_per_layer is a host array[L] (or NULL = no events).
+ * Same kernels, same launch order, same results; the only extra work is the event records. */
+lexi_status lexi_moe_stack_forward_profiled(const lexi_layer_t* layers, int32_t L, const int32_t* k_vec,
+                                            const void* x, int64_t x_layer_stride, void* y, int64_t y_layer_stride,
+                                            int32_t y_dtype, int32_t T, int32_t mode, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream,
+                                            const lexi_routing_out_t* dbg_per_layer,
+                                            const lexi_stage_events_t* events_per_layer);
+
 /* Static description of a status code. */
 const char* lexi_strerror(int32_t status);
 

@@ -18,8 +18,10 @@ LEXI_OK = 0
 LEXI_F32, LEXI_BF16 = 0, 1
 SHARED_NONE, SHARED_UNGATED, SHARED_SIGMOID = 0, 1, 2
 
-EXPORTS = ("lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward", "lexi_strerror",
-           "lexi_moe_version")
+EXPORTS = ("lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward",
+           "lexi_moe_stack_forward_profiled", "lexi_strerror", "lexi_moe_version")
+N_STAGE_EVENTS = 6
+STAGE_NAMES = ("routing", "gate_up", "down", "shared", "combine")
 
 
 class LexiError(RuntimeError):
@@ -42,6 +44,10 @@ class lexi_routing_out_t(ctypes.Structure):
                 ("offsets", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("inv_perm", ctypes.c_void_p)]
 
 
+class lexi_stage_events_t(ctypes.Structure):
+    _fields_ = [("ev", ctypes.c_void_p * N_STAGE_EVENTS)]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_02753_amd.build` "
@@ -56,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.lexi_moe_stack_forward.restype = i32
     lib.lexi_moe_stack_forward.argtypes = [ctypes.POINTER(lexi_layer_t), i32, ctypes.POINTER(i32), vp, i64, vp, i64,
                                            i32, i32, i32, vp, sz, vp, ctypes.POINTER(lexi_routing_out_t)]
+    lib.lexi_moe_stack_forward_profiled.restype = i32
+    lib.lexi_moe_stack_forward_profiled.argtypes = lib.lexi_moe_stack_forward.argtypes + [ctypes.POINTER(lexi_stage_events_t)]
     lib.lexi_strerror.restype = ctypes.c_char_p
     lib.lexi_strerror.argtypes = [i32]
     lib.lexi_moe_version.restype = ctypes.c_char_p
@@ -164,8 +172,10 @@ def lexi_moe_layer_forward(layer: Layer, x: torch.Tensor, y: torch.Tensor, k: in
 
 def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: torch.Tensor, y: torch.Tensor,
                            workspace: torch.Tensor, routing: Optional[Sequence[RoutingOut]] = None,
-                           stream: Optional[torch.cuda.Stream] = None, layer_array=None) -> None:
-    """Stack of L layers with the per-layer k vector.  x: [T][d] (shared by all layers) or [L][T][d]; y: [L][T][d]."""
+                           stream: Optional[torch.cuda.Stream] = None, layer_array=None, stage_events=None) -> None:
+    """Stack of L layers with the per-layer k vector.  x: [T][d] (shared by all layers) or [L][T][d]; y: [L][T][d].
+
+    stage_events: None, or a StageEvents object; then the profiled entry point records its events."""
     L = len(layers)
     T = int(x.shape[-2])
     x_stride = 0 if x.dim() == 2 else int(x.stride(0))
@@ -177,7 +187,32 @@ def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: tor
         for i, r in enumerate(routing):
             dbg[i] = r.c
     arr = layer_array if layer_array is not None else _layer_array(layers)
-    st = _lib.lexi_moe_stack_forward(arr, L, kv, _dp(x), x_stride, _dp(y), y_stride, _dtype_code(y.dtype), T, 0,
-                                     _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg)
+    if stage_events is not None:
+        st = _lib.lexi_moe_stack_forward_profiled(arr, L, kv, _dp(x), x_stride, _dp(y), y_stride, _dtype_code(y.dtype),
+                                                  T, 0, _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg,
+                                                  stage_events.c)
+    else:
+        st = _lib.lexi_moe_stack_forward(arr, L, kv, _dp(x), x_stride, _dp(y), y_stride, _dtype_code(y.dtype), T, 0,
+                                         _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg)
     if st != LEXI_OK:
         raise LexiError(st, "lexi_moe_stack_forward")
+
+
+class StageEvents:
+    """L x 6 HIP events (created through torch) that the profiled stack entry point records between stages."""
+
+    def __init__(self, L: int):
+        self.L = L
+        self.events = [[torch.cuda.Event(enable_timing=True) for _ in range(N_STAGE_EVENTS)] for _ in range(L)]
+        for row in self.events:          # torch creates the underlying hipEvent_t on the first record
+            for e in row:
+                e.record()
+        torch.cuda.synchronize()
+        self.c = (lexi_stage_events_t * L)()
+        for l, row in enumerate(self.events):
+            for i, e in enumerate(row):
+                self.c[l].ev[i] = e.cuda_event
+
+    def stage_ms(self):
+        """After a synchronize: per-layer list of the 5 stage durations in milliseconds."""
+        return [[row[i].elapsed_time(row[i + 1]) for i in range(N_STAGE_EVENTS - 1)] for row in self.events]

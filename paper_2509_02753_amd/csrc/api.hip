@@ -27,7 +27,7 @@ struct Carver {
 
 struct Workspace {
     int32_t *topk_idx, *local_rank, *blk_hist, *counts, *offsets, *perm, *inv_perm, *row_token, *sched, *sched_count;
-    float *gates, *y_slot, *y_shared, *coef;
+    float *gates, *partial, *y_slot, *y_shared, *coef;
     void *act, *act_shared;
     int max_tiles;
     size_t bytes;
@@ -40,6 +40,7 @@ Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
     const size_t es = ly.dtype == LEXI_BF16 ? 2 : 4;
     const size_t nblk = ((size_t)T + 7) / 8;  // router blocks never hold fewer than 8 tokens
     w.max_tiles = (int)((A + kTileTokens - 1) / kTileTokens) + ly.E;
+    w.partial = c.take<float>((size_t)(ly.d / 128) * T * 64);
     w.topk_idx = c.take<int32_t>(A);
     w.gates = c.take<float>(A);
     w.local_rank = c.take<int32_t>(A);
@@ -105,7 +106,12 @@ lexi_status check_call(const lexi_layer_t* ly, const void* x, const void* y, int
 
 // One layer, arguments already validated.
 lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_dtype, int32_t T, int32_t k,
-                      void* workspace, hipStream_t s, const lexi_routing_out_t* dbg) {
+                      void* workspace, hipStream_t s, const lexi_routing_out_t* dbg,
+                      const lexi_stage_events_t* events = nullptr) {
+    auto mark = [&](int i) {
+        if (events && events->ev[i]) (void)hipEventRecord((hipEvent_t)events->ev[i], s);
+    };
+    mark(0);
     Workspace w = carve(ly, T, k, workspace);
     const bool bf = ly.dtype == LEXI_BF16;
     // routing results land directly in the caller's arrays when those are given
@@ -121,22 +127,25 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     RoutingArgs r{};
     r.x = x; r.is_bf16 = bf; r.w_router = ly.w_router; r.bias = ly.router_bias;
     r.T = T; r.d = ly.d; r.E = ly.E; r.k = k; r.tile_tokens = kTileTokens;
-    r.topk_idx = w.topk_idx; r.gates = w.gates; r.local_rank = w.local_rank; r.blk_hist = w.blk_hist;
+    r.partial = w.partial; r.topk_idx = w.topk_idx; r.gates = w.gates; r.local_rank = w.local_rank; r.blk_hist = w.blk_hist;
     r.counts = w.counts; r.offsets = w.offsets; r.perm = w.perm; r.inv_perm = w.inv_perm; r.row_token = w.row_token;
     r.sched = w.sched; r.sched_count = w.sched_count;
     if (launch_routing(r, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+    mark(1);
 
     FfnArgs g{};
     g.is_bf16 = bf; g.in = x; g.row_token = w.row_token; g.w0 = ly.w_gate; g.w1 = ly.w_up; g.K = ly.d;
     g.features = ly.F; g.M = T * k; g.max_tiles = w.max_tiles; g.tile_tokens = kTileTokens; g.sched = w.sched;
     g.sched_count = w.sched_count; g.out = w.act;
     if (launch_gateup(g, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+    mark(2);
 
     FfnArgs dn{};
     dn.is_bf16 = bf; dn.in = w.act; dn.row_token = nullptr; dn.w0 = ly.w_down; dn.w1 = nullptr; dn.K = ly.F;
     dn.features = ly.d; dn.M = T * k; dn.max_tiles = w.max_tiles; dn.tile_tokens = kTileTokens; dn.sched = w.sched;
     dn.sched_count = w.sched_count; dn.out = w.y_slot;
     if (launch_down(dn, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+    mark(3);
 
     if (ly.F_shared > 0) {
         const int dense_tiles = (T + kTileTokens - 1) / kTileTokens;
@@ -155,12 +164,15 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
             return LEXI_ERR_LAUNCH;
     }
 
+    mark(4);
+
     CombineArgs c{};
     c.y_slot = w.y_slot; c.inv_perm = w.inv_perm; c.gates = w.gates;
     c.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr;
     c.shared_coef = ly.shared_kind == LEXI_SHARED_SIGMOID ? w.coef : nullptr;
     c.T = T; c.d = ly.d; c.k = k; c.y = y; c.y_bf16 = y_dtype == LEXI_BF16;
     if (launch_combine(c, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+    mark(5);
     return LEXI_OK;
 }
 
@@ -187,10 +199,12 @@ lexi_status lexi_moe_layer_forward(const lexi_layer_t* layer, const void* x, voi
     return run_layer(*layer, x, y, y_dtype, T, k, workspace, (hipStream_t)hip_stream, dbg);
 }
 
-lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const int32_t* k_vec, const void* x,
-                                   int64_t x_layer_stride, void* y, int64_t y_layer_stride, int32_t y_dtype,
-                                   int32_t T, int32_t mode, void* workspace, size_t workspace_bytes,
-                                   void* hip_stream, const lexi_routing_out_t* dbg_per_layer) {
+lexi_status lexi_moe_stack_forward_profiled(const lexi_layer_t* layers, int32_t L, const int32_t* k_vec,
+                                            const void* x, int64_t x_layer_stride, void* y, int64_t y_layer_stride,
+                                            int32_t y_dtype, int32_t T, int32_t mode, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream,
+                                            const lexi_routing_out_t* dbg_per_layer,
+                                            const lexi_stage_events_t* events_per_layer) {
     if (!layers || !k_vec) return LEXI_ERR_NULL;
     if (L < 1 || x_layer_stride < 0 || y_layer_stride < 0) return LEXI_ERR_SHAPE;
     if (mode != 0) return LEXI_ERR_DTYPE;
@@ -212,10 +226,19 @@ lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const 
         const void* xl = (const char*)x + (size_t)l * x_layer_stride * xes;
         void* yl = (char*)y + (size_t)l * y_layer_stride * yes;
         lexi_status st = run_layer(layers[l], xl, yl, y_dtype, T, k_vec[l], workspace, (hipStream_t)hip_stream,
-                                   dbg_per_layer ? &dbg_per_layer[l] : nullptr);
+                                   dbg_per_layer ? &dbg_per_layer[l] : nullptr,
+                                   events_per_layer ? &events_per_layer[l] : nullptr);
         if (st != LEXI_OK) return st;
     }
     return LEXI_OK;
+}
+
+lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const int32_t* k_vec, const void* x,
+                                   int64_t x_layer_stride, void* y, int64_t y_layer_stride, int32_t y_dtype,
+                                   int32_t T, int32_t mode, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream, const lexi_routing_out_t* dbg_per_layer) {
+    return lexi_moe_stack_forward_profiled(layers, L, k_vec, x, x_layer_stride, y, y_layer_stride, y_dtype, T, mode,
+                                           workspace, workspace_bytes, hip_stream, dbg_per_layer, nullptr);
 }
 
 const char* lexi_strerror(int32_t status) {

@@ -11,6 +11,7 @@ struct RoutingArgs {
     const float* bias;        // [E] or null
     int T, d, E, k;
     int tile_tokens;          // token-tile height the grouped GEMM schedule is built for
+    float* partial;           // [d/128][T][64] segment partials of the logits
     int32_t* topk_idx;        // [T*k]
     float* gates;             // [T*k]
     int32_t* local_rank;      // [T*k]  rank of the assignment inside its router block, per expert

@@ -7,23 +7,164 @@
 namespace lexi {
 
 // ---------------------------------------------------------------------------------------------------------
-// router_topk_kernel
-//   One lane per expert (E <= 64), TM tokens per wave, WAVES waves per workgroup.
-//   logits: the fixed order -- per 128-segment a chain of fused multiply-adds from +0, partials added in
-//   ascending order, bias last.  The chain operand x[t][j] is wave-uniform (scalar loads), W[j][e] comes from an
-//   LDS copy of the current segment shared by the waves of the workgroup.
+// The fp32 logit of (token t, expert e) has ONE defined evaluation order: d is cut into segments of 128; inside a
+// segment the partial starts at +0 and takes one fused multiply-add per element, ascending; the partials are added
+// in ascending segment order; the bias is added last.  The segment partials are independent chains, which is where
+// the parallelism comes from: partial[seg][t][e] is produced by the two kernels below (a register-tiled one for
+// prefill-sized T, a latency-oriented one for decode-sized T) and summed in order by topk_kernel.
+// ---------------------------------------------------------------------------------------------------------
+
+// router_partial_kernel: workgroup = 256 tokens x 64 experts x one segment, 4 waves.  A wave owns 64 tokens; a lane
+// owns an 8 (tokens) x 8 (experts) block of accumulators, so per j it reads 8 x-values and 8 w-values from LDS for 64
+// fused multiply-adds.  x is staged through LDS transposed ([j][token], fp32) by the thread that owns the token row,
+// W[j][e] row-major; the next 32-j stage is prefetched into registers while the current one is consumed.
+template <bool IS_BF16>
+__global__ void __launch_bounds__(256)
+router_partial_kernel(const void* __restrict__ x, const float* __restrict__ w_router, int T, int d, int E,
+                      float* __restrict__ partial) {
+    constexpr int SJ = 32;                      // j per LDS stage
+    constexpr int NSTAGE = kRouterSegment / SJ;
+    __shared__ __attribute__((aligned(16))) float xs[4][SJ][64];
+    __shared__ __attribute__((aligned(16))) float wsm[SJ][64];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int eg = lane & 7, tg = lane >> 3;
+    const int seg = blockIdx.y;
+    const int tok_base = blockIdx.x * 256;
+    const int my_row = min(tok_base + tid, T - 1);  // rows past T re-read the last row; never stored
+    const int j_seg = seg * kRouterSegment;
+
+    u32x4_t xr[IS_BF16 ? 4 : 8];
+    float wr[8];
+    auto load_stage = [&](int st) {
+        const int j0 = j_seg + st * SJ;
+        if (IS_BF16) {
+            const u32x4_t* p = (const u32x4_t*)((const bf16_t*)x + (size_t)my_row * d + j0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xr[i] = p[i];
+        } else {
+            const u32x4_t* p = (const u32x4_t*)((const float*)x + (size_t)my_row * d + j0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xr[i] = p[i];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int i = tid + 256 * r, jj = i >> 6, e = i & 63;
+            wr[r] = (e < E) ? w_router[(size_t)(j0 + jj) * E + e] : 0.0f;
+        }
+    };
+    auto store_stage = [&]() {
+        if (IS_BF16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    xs[wave][8 * i + 2 * c][lane] = __uint_as_float(xr[i][c] << 16);
+                    xs[wave][8 * i + 2 * c + 1][lane] = __uint_as_float(xr[i][c] & 0xFFFF0000u);
+                }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) xs[wave][4 * i + c][lane] = __uint_as_float(xr[i][c]);
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int i = tid + 256 * r;
+            wsm[i >> 6][i & 63] = wr[r];
+        }
+    };
+
+    float acc[8][8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
+
+    load_stage(0);
+    for (int st = 0; st < NSTAGE; ++st) {
+        __syncthreads();
+        store_stage();
+        __syncthreads();
+        if (st + 1 < NSTAGE) load_stage(st + 1);
+#pragma unroll 4
+        for (int jj = 0; jj < SJ; ++jj) {
+            const f32x4_t x0 = *(const f32x4_t*)&xs[wave][jj][8 * tg];
+            const f32x4_t x1 = *(const f32x4_t*)&xs[wave][jj][8 * tg + 4];
+            const f32x4_t w0 = *(const f32x4_t*)&wsm[jj][8 * eg];
+            const f32x4_t w1 = *(const f32x4_t*)&wsm[jj][8 * eg + 4];
+#pragma unroll
+            for (int a = 0; a < 8; ++a) {
+                const float xv = a < 4 ? x0[a & 3] : x1[a & 3];
+#pragma unroll
+                for (int b = 0; b < 8; ++b) acc[a][b] = __builtin_fmaf(xv, b < 4 ? w0[b & 3] : w1[b & 3], acc[a][b]);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+        const int t = tok_base + wave * 64 + 8 * tg + a;
+        if (t < T) {
+            float* o = partial + ((size_t)seg * T + t) * 64 + 8 * eg;
+            f32x4_t v0 = {acc[a][0], acc[a][1], acc[a][2], acc[a][3]};
+            f32x4_t v1 = {acc[a][4], acc[a][5], acc[a][6], acc[a][7]};
+            *(f32x4_t*)o = v0;
+            *(f32x4_t*)(o + 4) = v1;
+        }
+    }
+}
+
+// router_partial_small_kernel: one wave = one segment x TW tokens, lane = expert.  The segment's 128 router weights
+// of the lane's expert sit in registers (128 coalesced loads in flight at once); the token's x values are
+// wave-uniform (scalar loads), so each token costs one 128-long chain of fused multiply-adds.
+template <bool IS_BF16, int TW>
+__global__ void __launch_bounds__(64)
+router_partial_small_kernel(const void* __restrict__ x, const float* __restrict__ w_router, int T, int d, int E,
+                            float* __restrict__ partial) {
+    const int lane = threadIdx.x;
+    const int seg = blockIdx.x;
+    const int t0 = blockIdx.y * TW;
+    const int j_seg = seg * kRouterSegment;
+    float w[kRouterSegment];
+#pragma unroll
+    for (int jj = 0; jj < kRouterSegment; ++jj) w[jj] = (lane < E) ? w_router[(size_t)(j_seg + jj) * E + lane] : 0.0f;
+    for (int m = 0; m < TW; ++m) {
+        const int t = t0 + m;
+        if (t >= T) break;
+        float acc = 0.0f;
+        if (IS_BF16) {
+            const uint32_t* xp = (const uint32_t*)((const bf16_t*)x + (size_t)t * d + j_seg);
+#pragma unroll
+            for (int i = 0; i < kRouterSegment / 2; ++i) {
+                const uint32_t p = xp[i];
+                acc = __builtin_fmaf(__uint_as_float(p << 16), w[2 * i], acc);
+                acc = __builtin_fmaf(__uint_as_float(p & 0xFFFF0000u), w[2 * i + 1], acc);
+            }
+        } else {
+            const float* xp = (const float*)x + (size_t)t * d + j_seg;
+#pragma unroll
+            for (int i = 0; i < kRouterSegment; ++i) acc = __builtin_fmaf(xp[i], w[i], acc);
+        }
+        partial[((size_t)seg * T + t) * 64 + lane] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// topk_kernel: one lane per expert (E <= 64), TM tokens per wave, WAVES waves per workgroup.
+//   logit = ordered sum of the segment partials, then the bias.
 //   top-k: k rounds of {wave maximum by DPP, ballot of the lanes that hold it, lowest set bit} -- the lowest
 //   index among equal logits wins; comparisons are on floats, so +0 == -0.
+//   gates: softmax over the k selected logits.
 //   Each selected (token, slot) also gets its rank among the workgroup's earlier assignments to the same expert
 //   (tokens ascending), which is what makes the later scatter a stable counting sort without atomics.
 // ---------------------------------------------------------------------------------------------------------
-template <bool IS_BF16, int TM, int WAVES>
+template <int TM, int WAVES>
 __global__ void __launch_bounds__(WAVES * 64)
-router_topk_kernel(const void* __restrict__ x, const float* __restrict__ w_router, const float* __restrict__ bias,
-                   int T, int d, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ gates,
-                   int32_t* __restrict__ local_rank, int32_t* __restrict__ blk_hist) {
+topk_kernel(const float* __restrict__ partial, const float* __restrict__ bias, int T, int nseg, int E, int k,
+            int32_t* __restrict__ topk_idx, float* __restrict__ gates, int32_t* __restrict__ local_rank,
+            int32_t* __restrict__ blk_hist) {
     constexpr int TB = TM * WAVES;
-    __shared__ float w_lds[kRouterSegment * 64];
     __shared__ int32_t wave_cnt[WAVES][64];
 
     const int lane = threadIdx.x & 63;
@@ -32,52 +173,17 @@ router_topk_kernel(const void* __restrict__ x, const float* __restrict__ w_route
 
     float total[TM];
 #pragma unroll
-    for (int m = 0; m < TM; ++m) total[m] = 0.0f;
-
-    const int nseg = d / kRouterSegment;
-    for (int seg = 0; seg < nseg; ++seg) {
-        __syncthreads();
-        for (int i = threadIdx.x; i < kRouterSegment * 64; i += WAVES * 64) {
-            const int jj = i >> 6, e = i & 63;
-            w_lds[i] = (e < E) ? w_router[(size_t)(seg * kRouterSegment + jj) * E + e] : 0.0f;
-        }
-        __syncthreads();
-
-        float acc[TM];
-#pragma unroll
-        for (int m = 0; m < TM; ++m) acc[m] = 0.0f;
-
-        for (int jj = 0; jj < kRouterSegment; jj += 8) {
-            float w[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w[i] = w_lds[(jj + i) * 64 + lane];
-#pragma unroll
-            for (int m = 0; m < TM; ++m) {
-                int t = tok0 + m;
-                t = t < T ? t : T - 1;  // tail tokens recompute the last row; their results are never stored
-                const size_t base = (size_t)t * d + seg * kRouterSegment + jj;
-                float xv[8];
-                if (IS_BF16) {
-                    const u32x4_t p = *(const u32x4_t*)((const bf16_t*)x + base);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        xv[2 * i] = __uint_as_float(p[i] << 16);
-                        xv[2 * i + 1] = __uint_as_float(p[i] & 0xFFFF0000u);
-                    }
-                } else {
-                    const f32x4_t p0 = *(const f32x4_t*)((const float*)x + base);
-                    const f32x4_t p1 = *(const f32x4_t*)((const float*)x + base + 4);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) { xv[i] = p0[i]; xv[4 + i] = p1[i]; }
-                }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[m] = __builtin_fmaf(xv[i], w[i], acc[m]);
-            }
-        }
-#pragma unroll
-        for (int m = 0; m < TM; ++m) total[m] = (seg == 0) ? acc[m] : total[m] + acc[m];
+    for (int m = 0; m < TM; ++m) {
+        const int t = min(tok0 + m, T - 1);
+        total[m] = partial[(size_t)t * 64 + lane];
     }
-
+    for (int sg = 1; sg < nseg; ++sg) {
+#pragma unroll
+        for (int m = 0; m < TM; ++m) {
+            const int t = min(tok0 + m, T - 1);
+            total[m] = total[m] + partial[((size_t)sg * T + t) * 64 + lane];
+        }
+    }
     const bool lane_valid = lane < E;
     if (bias != nullptr) {
         const float b = lane_valid ? bias[lane] : 0.0f;
@@ -85,7 +191,6 @@ router_topk_kernel(const void* __restrict__ x, const float* __restrict__ w_route
         for (int m = 0; m < TM; ++m) total[m] = total[m] + b;
     }
 
-    // ---- top-k, gates, per-wave ranks ----
     int32_t cnt = 0;           // lane e: assignments to expert e made so far by this wave
     int32_t sel[TM], rnk[TM];  // lane s (< k): expert, gate and rank-in-wave of slot s of token m
     float gte[TM];
@@ -137,32 +242,50 @@ router_topk_kernel(const void* __restrict__ x, const float* __restrict__ w_route
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// scan_kernel (one wave): per expert, exclusive prefix of the block histograms (in place), counts, offsets, and
-// the token-tile schedule of the grouped GEMMs: tile i -> (expert, first row, rows).
+// scan_kernel (one workgroup of 16 waves): per expert, exclusive prefix of the block histograms (in place),
+// counts, offsets, and the token-tile schedule of the grouped GEMMs: tile i -> (expert, first row, rows).
+// Wave w scans its contiguous chunk of blocks, the chunk totals are combined through LDS.
 // ---------------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(1024)
 scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, int32_t* __restrict__ counts,
             int32_t* __restrict__ offsets, int32_t* __restrict__ sched, int32_t* __restrict__ sched_count) {
+    __shared__ int32_t chunk_tot[16][64];
     __shared__ int32_t s_cnt[64];
     __shared__ int32_t s_tiles[64];
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunk = (nblk + 15) / 16;
+    const int b0 = wave * chunk, b1 = min(nblk, b0 + chunk);
     int32_t running = 0;
-    for (int b = 0; b < nblk; ++b) {
+    for (int b = b0; b < b1; ++b) {
         const int32_t h = blk_hist[(size_t)b * 64 + lane];
         blk_hist[(size_t)b * 64 + lane] = running;
         running += h;
     }
-    const int32_t ntile = (running + tile_tokens - 1) / tile_tokens;
-    s_cnt[lane] = running;
-    s_tiles[lane] = ntile;
+    chunk_tot[wave][lane] = running;
     __syncthreads();
+    int32_t base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const int32_t c = chunk_tot[w][lane];
+        base += (w < wave) ? c : 0;
+        total += c;
+    }
+    if (base != 0)
+        for (int b = b0; b < b1; ++b) blk_hist[(size_t)b * 64 + lane] += base;
+    const int32_t ntile = (total + tile_tokens - 1) / tile_tokens;
+    if (wave == 0) {
+        s_cnt[lane] = total;
+        s_tiles[lane] = ntile;
+    }
+    __syncthreads();
+    if (wave != 0) return;
     int32_t off = 0, tile_base = 0;
     for (int e = 0; e < lane; ++e) { off += s_cnt[e]; tile_base += s_tiles[e]; }
     if (lane < E) {
-        counts[lane] = running;
+        counts[lane] = total;
         offsets[lane] = off;
         for (int i = 0; i < ntile; ++i) {
-            const int32_t rows = min(tile_tokens, running - i * tile_tokens);
+            const int32_t rows = min(tile_tokens, total - i * tile_tokens);
             int32_t* s = sched + (size_t)(tile_base + i) * 4;
             s[0] = lane;                     // expert
             s[1] = off + i * tile_tokens;    // first permuted row
@@ -172,7 +295,7 @@ scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, in
     }
     if (lane == 63) {
         // lanes >= E carry zero counts, so lane 63's exclusive sums plus its own are the totals
-        offsets[E] = off + running;
+        offsets[E] = off + total;
         sched_count[0] = tile_base + ntile;
     }
 }
@@ -199,35 +322,39 @@ permute_kernel(const int32_t* __restrict__ topk_idx, const int32_t* __restrict__
 // ---------------------------------------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------------------------------------
-int router_tokens_per_block(int T) {
-    if (T >= 256 * 32) return 32;
-    if (T >= 256 * 16) return 16;
-    return 8;
-}
+constexpr int kSmallRouterMaxT = 1024;  // at or below this many tokens the latency-oriented partial kernel runs
+
+int router_tokens_per_block(int T) { return T >= 2048 ? 32 : 8; }
 
 template <bool IS_BF16>
-static hipError_t launch_router_t(const RoutingArgs& a, hipStream_t s) {
-    const int tb = router_tokens_per_block(a.T);
-    const int nblk = (a.T + tb - 1) / tb;
-    if (tb == 32)
-        hipLaunchKernelGGL((router_topk_kernel<IS_BF16, 8, 4>), dim3(nblk), dim3(256), 0, s, a.x, a.w_router, a.bias, a.T,
-                           a.d, a.E, a.k, a.topk_idx, a.gates, a.local_rank, a.blk_hist);
-    else if (tb == 16)
-        hipLaunchKernelGGL((router_topk_kernel<IS_BF16, 8, 2>), dim3(nblk), dim3(128), 0, s, a.x, a.w_router, a.bias, a.T,
-                           a.d, a.E, a.k, a.topk_idx, a.gates, a.local_rank, a.blk_hist);
-    else
-        hipLaunchKernelGGL((router_topk_kernel<IS_BF16, 8, 1>), dim3(nblk), dim3(64), 0, s, a.x, a.w_router, a.bias, a.T,
-                           a.d, a.E, a.k, a.topk_idx, a.gates, a.local_rank, a.blk_hist);
+static hipError_t launch_partials(const RoutingArgs& a, hipStream_t s) {
+    const int nseg = a.d / kRouterSegment;
+    if (a.T <= kSmallRouterMaxT) {
+        constexpr int TW = 4;
+        hipLaunchKernelGGL((router_partial_small_kernel<IS_BF16, TW>), dim3(nseg, (a.T + TW - 1) / TW), dim3(64), 0, s,
+                           a.x, a.w_router, a.T, a.d, a.E, a.partial);
+    } else {
+        hipLaunchKernelGGL((router_partial_kernel<IS_BF16>), dim3((a.T + 255) / 256, nseg), dim3(256), 0, s, a.x,
+                           a.w_router, a.T, a.d, a.E, a.partial);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_routing(const RoutingArgs& a, hipStream_t s) {
-    hipError_t err = a.is_bf16 ? launch_router_t<true>(a, s) : launch_router_t<false>(a, s);
+    hipError_t err = a.is_bf16 ? launch_partials<true>(a, s) : launch_partials<false>(a, s);
     if (err != hipSuccess) return err;
+    const int nseg = a.d / kRouterSegment;
     const int tb = router_tokens_per_block(a.T);
     const int nblk = (a.T + tb - 1) / tb;
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(64), 0, s, a.blk_hist, nblk, a.E, a.tile_tokens, a.counts, a.offsets,
-                       a.sched, a.sched_count);
+    if (tb == 32)
+        hipLaunchKernelGGL((topk_kernel<8, 4>), dim3(nblk), dim3(256), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
+                           a.topk_idx, a.gates, a.local_rank, a.blk_hist);
+    else
+        hipLaunchKernelGGL((topk_kernel<8, 1>), dim3(nblk), dim3(64), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
+                           a.topk_idx, a.gates, a.local_rank, a.blk_hist);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, s, a.blk_hist, nblk, a.E, a.tile_tokens, a.counts,
+                       a.offsets, a.sched, a.sched_count);
     if ((err = hipGetLastError()) != hipSuccess) return err;
     const int A = a.T * a.k;
     hipLaunchKernelGGL(permute_kernel, dim3((A + 255) / 256), dim3(256), 0, s, a.topk_idx, a.local_rank, a.blk_hist,
