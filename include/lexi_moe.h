@@ -25,9 +25,14 @@
  *       x, y           [T][d]
  *       w_router       [d][E]   fp32 always (router runs in fp32)
  *       router_bias    [E]      fp32, added to the logits before selection, or NULL
- *       w_gate, w_up   [E][F][d]   one row = the input weights of one hidden feature
- *       w_down         [E][d][F]   one row = the input weights of one output feature
- *       ws_gate, ws_up [Fs][d],  ws_down [d][Fs],  w_shared_gate [d]
+ *       w_gate, w_up   E matrices [F][d]   one row = the input weights of one hidden feature
+ *       w_down         E matrices [d][F]   one row = the input weights of one output feature
+ *       ws_gate, ws_up one matrix [Fs][d],  ws_down one matrix [d][Fs],  w_shared_gate [d]
+ *     Every expert weight MATRIX W[R][K] (all of the above except w_shared_gate) is stored in the PACKED layout
+ *     the matrix cores read directly: W is cut into blocks of 16 rows x 32 columns, blocks ordered along K first,
+ *     then along R; inside a block the 8-element run (row i, columns 8q..8q+7) sits at run position q*16 + i:
+ *         index(r, k) = ((((r/16) * (K/32) + k/32) * 64 + ((k%32)/8) * 16 + r%16) * 8 + k%8
+ *     lexi_pack_weights converts row-major matrices into this layout (one-time, per checkpoint load).
  *     dtype LEXI_BF16: x, expert weights and the SwiGLU intermediate are bf16,
  *     accumulation is fp32.  dtype LEXI_F32: everything fp32.
  *   - Shape limits: 1 <= E <= 64, d % 128 == 0, F % 64 == 0, F_shared % 64 == 0,
@@ -75,12 +80,12 @@ typedef struct {
     int32_t shared_kind;        /* lexi_shared_kind */
     const float* w_router;      /* [d][E] */
     const float* router_bias;   /* [E] or NULL */
-    const void* w_gate;         /* [E][F][d] */
-    const void* w_up;           /* [E][F][d] */
-    const void* w_down;         /* [E][d][F] */
-    const void* ws_gate;        /* [Fs][d] or NULL */
-    const void* ws_up;          /* [Fs][d] or NULL */
-    const void* ws_down;        /* [d][Fs] or NULL */
+    const void* w_gate;         /* E packed matrices [F][d] */
+    const void* w_up;           /* E packed matrices [F][d] */
+    const void* w_down;         /* E packed matrices [d][F] */
+    const void* ws_gate;        /* packed [Fs][d] or NULL */
+    const void* ws_up;          /* packed [Fs][d] or NULL */
+    const void* ws_down;        /* packed [d][Fs] or NULL */
     const void* w_shared_gate;  /* [d] (LEXI_SHARED_SIGMOID) or NULL */
 } lexi_layer_t;
 
@@ -93,6 +98,12 @@ typedef struct {
     int32_t* perm;      /* [T*k]   position -> assignment t*k+s */
     int32_t* inv_perm;  /* [T*k]   assignment -> position */
 } lexi_routing_out_t;
+
+/* Re-layout of expert weights (the E_i of Sec. 2) from row-major into the packed layout described above.
+ *   src: device, n_matrices row-major matrices [rows][K] back to back; dst: device, same size, must not overlap src;
+ *   rows % 16 == 0, K % 32 == 0, dtype = lexi_dtype of the elements.  Asynchronous on hip_stream. */
+lexi_status lexi_pack_weights(const void* src, void* dst, int64_t n_matrices, int32_t rows, int32_t K, int32_t dtype,
+                              void* hip_stream);
 
 /* Bytes of device workspace that any call with these layers, T <= T_max and k <= k_max needs.
  * layers: host array[L].  Returns 0 if an argument is invalid. */

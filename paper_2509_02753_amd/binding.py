@@ -18,7 +18,7 @@ LEXI_OK = 0
 LEXI_F32, LEXI_BF16 = 0, 1
 SHARED_NONE, SHARED_UNGATED, SHARED_SIGMOID = 0, 1, 2
 
-EXPORTS = ("lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward",
+EXPORTS = ("lexi_pack_weights", "lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward",
            "lexi_moe_stack_forward_profiled", "lexi_strerror", "lexi_moe_version")
 N_STAGE_EVENTS = 6
 STAGE_NAMES = ("routing", "gate_up", "down", "shared", "combine")
@@ -54,6 +54,8 @@ def _load() -> ctypes.CDLL:
                           "(there is no fallback implementation)")
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    lib.lexi_pack_weights.restype = i32
+    lib.lexi_pack_weights.argtypes = [vp, vp, i64, i32, i32, i32, vp]
     lib.lexi_moe_workspace_bytes.restype = sz
     lib.lexi_moe_workspace_bytes.argtypes = [ctypes.POINTER(lexi_layer_t), i32, i32, i32]
     lib.lexi_moe_layer_forward.restype = i32
@@ -85,6 +87,11 @@ def _dp(t: Optional[torch.Tensor]):
     return None if t is None else t.data_ptr()
 
 
+def _stream_ptr(stream: Optional[torch.cuda.Stream]):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
 def _dtype_code(t: torch.dtype) -> int:
     if t == torch.float32:
         return LEXI_F32
@@ -93,8 +100,24 @@ def _dtype_code(t: torch.dtype) -> int:
     raise ValueError(f"unsupported dtype {t}")
 
 
+def lexi_pack_weights(w: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Row-major [..., rows, K] expert weights -> a new tensor of the same shape holding the packed layout."""
+    if not (w.is_cuda and w.is_contiguous() and w.dim() >= 2):
+        raise ValueError("lexi_pack_weights: contiguous CUDA tensor [..., rows, K] required")
+    rows, K = int(w.shape[-2]), int(w.shape[-1])
+    n = w.numel() // (rows * K)
+    out = torch.empty_like(w)
+    st = _lib.lexi_pack_weights(_dp(w), _dp(out), n, rows, K, _dtype_code(w.dtype), _stream_ptr(stream))
+    if st != LEXI_OK:
+        raise LexiError(st, "lexi_pack_weights")
+    return out
+
+
 class Layer:
-    """Host-side lexi_layer_t plus references that keep its device tensors alive."""
+    """Host-side lexi_layer_t plus references that keep its device tensors alive.
+
+    The constructor takes expert weight matrices already in the packed layout; `from_tensors` takes row-major
+    tensors and packs them with the library's own kernel."""
 
     def __init__(self, w_router, w_gate, w_up, w_down, router_bias=None, ws_gate=None, ws_up=None, ws_down=None,
                  w_shared_gate=None, shared_kind: Optional[int] = None):
@@ -116,9 +139,13 @@ class Layer:
 
     @classmethod
     def from_tensors(cls, tensors: Dict[str, Optional[torch.Tensor]], shared_kind: Optional[int] = None) -> "Layer":
-        return cls(tensors["w_router"], tensors["w_gate"], tensors["w_up"], tensors["w_down"],
-                   router_bias=tensors.get("router_bias"), ws_gate=tensors.get("ws_gate"), ws_up=tensors.get("ws_up"),
-                   ws_down=tensors.get("ws_down"), w_shared_gate=tensors.get("w_shared_gate"), shared_kind=shared_kind)
+        """tensors: row-major w_gate/w_up [E][F][d], w_down [E][d][F], ws_gate/ws_up [Fs][d], ws_down [d][Fs], ..."""
+        def pk(name):
+            t = tensors.get(name)
+            return None if t is None else lexi_pack_weights(t)
+        return cls(tensors["w_router"], pk("w_gate"), pk("w_up"), pk("w_down"),
+                   router_bias=tensors.get("router_bias"), ws_gate=pk("ws_gate"), ws_up=pk("ws_up"),
+                   ws_down=pk("ws_down"), w_shared_gate=tensors.get("w_shared_gate"), shared_kind=shared_kind)
 
 
 class RoutingOut:
@@ -152,11 +179,6 @@ def alloc_workspace(layers: Sequence[Layer], T_max: int, k_max: int, device="cud
     if n == 0:
         raise LexiError(-2, "lexi_moe_workspace_bytes")
     return torch.empty(n, dtype=torch.uint8, device=device)
-
-
-def _stream_ptr(stream: Optional[torch.cuda.Stream]):
-    s = torch.cuda.current_stream() if stream is None else stream
-    return ctypes.c_void_p(s.cuda_stream)
 
 
 def lexi_moe_layer_forward(layer: Layer, x: torch.Tensor, y: torch.Tensor, k: int, workspace: torch.Tensor,

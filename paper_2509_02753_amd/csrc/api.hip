@@ -180,6 +180,22 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
 
 extern "C" {
 
+lexi_status lexi_pack_weights(const void* src, void* dst, int64_t n_matrices, int32_t rows, int32_t K, int32_t dtype,
+                              void* hip_stream) {
+    if (dtype != LEXI_F32 && dtype != LEXI_BF16) return LEXI_ERR_DTYPE;
+    if (n_matrices < 0 || rows < 16 || rows % 16 != 0 || K < 32 || K % 32 != 0) return LEXI_ERR_SHAPE;
+    if (n_matrices == 0) return LEXI_OK;
+    if (!src || !dst) return LEXI_ERR_NULL;
+    if (misaligned(src) || misaligned(dst) || (dtype == LEXI_F32 && (((uintptr_t)src | (uintptr_t)dst) & 31u)))
+        return LEXI_ERR_ALIGN;
+    const size_t bytes = (size_t)n_matrices * rows * K * (dtype == LEXI_BF16 ? 2 : 4);
+    const char *a = (const char*)src, *b = (const char*)dst;
+    if (a < b + bytes && b < a + bytes) return LEXI_ERR_SHAPE;  // overlapping buffers
+    if (launch_pack(src, dst, n_matrices, rows, K, dtype == LEXI_BF16, (hipStream_t)hip_stream) != hipSuccess)
+        return LEXI_ERR_LAUNCH;
+    return LEXI_OK;
+}
+
 size_t lexi_moe_workspace_bytes(const lexi_layer_t* layers, int32_t L, int32_t T_max, int32_t k_max) {
     if (!layers || L < 1 || T_max < 0 || k_max < 1) return 0;
     size_t need = 256;

@@ -29,7 +29,8 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
-__device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
+// silu(z) = z * sigmoid(z); hardware exp2 and reciprocal (about 1 ulp each), ample for a bf16 result
+__device__ __forceinline__ float silu(float z) { return z * __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 
 // Element `i` of a tensor stored as fp32 (IS_BF16 = false) or bf16, widened exactly.
 template <bool IS_BF16>

@@ -2,10 +2,10 @@
 // that holds nearly all parameters and FLOPs).  bf16 operands on MFMA with fp32 accumulation; a plain fp32 kernel
 // covers fp32 layers.
 //
-// Orientation: the weight tile is the MFMA "A" operand (its 32 rows are features), the token tile is the "B"
-// operand (its 32 columns are tokens).  In the 32x32 accumulator a lane then owns ONE token (column lane%32) and
-// four groups of 4 consecutive features (rows 8g + 4*(lane/32) + 0..3), so the epilogue writes 8- or 16-byte
-// runs along the feature axis, and SwiGLU pairs the gate and up accumulators register by register.
+// Orientation: the weight block is the MFMA "A" operand (its 16 rows are features), the token block is the "B"
+// operand (its 16 columns are tokens).  In the 16x16 accumulator a lane then owns ONE token (column lane%16) and
+// 4 consecutive features (rows 4*(lane/16) + 0..3), so the epilogue writes 8- or 16-byte runs along the feature
+// axis, and SwiGLU pairs the gate and up accumulators register by register.
 #include "kernels.hpp"
 
 namespace lexi {
@@ -13,6 +13,15 @@ namespace lexi {
 constexpr int BK = 64;         // K elements per LDS stage
 constexpr int LDS_PAD = 8;     // bf16 elements of padding per LDS row (16 B): spreads the 16-byte operand reads over banks
 constexpr int LDS_LD = BK + LDS_PAD;
+
+// Expert weight matrices W[R][K] (R output features, K inputs) are stored in the MFMA-native "packed" layout:
+// the matrix is cut into blocks of 16 rows x 32 K elements; a block is 64 runs of 8 consecutive K elements, run
+// (q, i) = (K-octet q of the block, row i of the block) at position q*16 + i; blocks follow each other along K, then
+// along R.  A wave-wide 16-byte-per-lane load of one block is therefore 1 KB of contiguous memory and is, as it
+// stands, the A operand of v_mfma_f32_16x16x32_bf16 (lane = q*16 + i).
+__host__ __device__ __forceinline__ size_t packed_index(int r, int k, int K) {
+    return ((((size_t)(r >> 4) * (K >> 5) + (k >> 5)) * 64 + ((k & 31) >> 3) * 16 + (r & 15)) << 3) + (k & 7);
+}
 
 struct TileInfo {
     int expert, row0, rows;
@@ -36,20 +45,24 @@ __device__ __forceinline__ bool fetch_tile(const int32_t* sched, const int32_t* 
 
 // ---------------------------------------------------------------------------------------------------------
 // ffn_mfma_kernel<GATEUP>
-//   Workgroup tile: 128 weight rows x 128 tokens, 4 waves as 2 (feature halves) x 2 (token halves); each wave owns
-//   2 x 2 accumulator blocks of 32 x 32.  K advances in stages of 64 through double-buffered LDS.
-//   GATEUP: weight rows 0..63 are gate rows f0..f0+63, rows 64..127 the matching up rows; the wave's two feature
-//   blocks are (gate, up) of the same 32 features, so the epilogue is silu(gate)*up -> bf16 act[row][f].
-//   DOWN:   weight rows are 128 consecutive output features; the epilogue stores fp32 out[row][j].
+//   Workgroup = 4 waves; token tile = 128 rows shared by all waves through double-buffered LDS; each wave owns its
+//   own 64 weight rows (4 feature blocks of 16) against all 128 tokens (8 token blocks): 32 accumulator blocks of
+//   16 x 16 (v_mfma_f32_16x16x32_bf16), i.e. a 256 x 128 workgroup tile in at most 256 registers per lane, so two
+//   workgroups share a CU and one's prologue/epilogue overlaps the other's MFMA loop.  Weight rows are not shared between waves
+//   and are stored in the packed layout, so their MFMA operand fragments go straight from global memory to
+//   registers as fully coalesced 1 KB wave loads; only the token tile passes through LDS (8 fragment reads per 32 MFMAs).
+//   GATEUP: a wave's blocks 0,1 are gate rows g0..g0+31 and blocks 2,3 the matching up rows, so the epilogue is
+//   silu(gate)*up -> bf16 act[row][f]; the workgroup covers 128 hidden features.
+//   DOWN:   a wave's blocks are 64 consecutive output features; the epilogue stores fp32 out[row][j].
 //   Token rows are gathered through row_token (no permuted copy of X is ever materialised).
+//   Waves whose feature range lies past `features` (ragged last workgroup column) only help staging the tokens.
 // ---------------------------------------------------------------------------------------------------------
 template <bool GATEUP>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_token, const bf16_t* __restrict__ w0,
                 const bf16_t* __restrict__ w1, int K, int features, int M, int tile_tokens,
                 const int32_t* __restrict__ sched, const int32_t* __restrict__ sched_count, void* __restrict__ out) {
-    constexpr int TT = 128;
-    __shared__ __attribute__((aligned(16))) bf16_t lds_w[2][128 * LDS_LD];
+    constexpr int TT = 128, TB = TT / 16, WB = 4, KS = BK / 32;
     __shared__ __attribute__((aligned(16))) bf16_t lds_x[2][TT * LDS_LD];
 
     TileInfo ti;
@@ -58,114 +71,116 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wf = wave & 1, wt = wave >> 1;
-    const int f0 = blockIdx.x * (GATEUP ? 64 : 128);  // first output feature of this workgroup
+    const int wave_f0 = blockIdx.x * (GATEUP ? 128 : 256) + wave * (GATEUP ? 32 : 64);  // first output feature
+    const bool active = wave_f0 < features;
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int koff = kq * 8;
 
-    // ---- global -> register staging: thread owns 16-byte chunk (tid % 8) of rows tid/8 + 32p ----
+    // ---- weight fragment pointers: feature block fb of this wave is 16 packed rows; one K-step of 32 is one 1 KB
+    //      block, lane reads its 16 bytes at lane*8 elements; successive K-steps are 512 elements apart.
+    const bf16_t* aptr[WB];
+#pragma unroll
+    for (int fb = 0; fb < WB; ++fb) {
+        int row;
+        const bf16_t* base = w0;
+        if (GATEUP) {
+            row = wave_f0 + 16 * (fb & 1);
+            if (fb >= 2) base = w1;
+        } else {
+            row = wave_f0 + 16 * fb;
+        }
+        row = active ? row : 0;
+        aptr[fb] = base + ((size_t)ti.expert * (features >> 4) + (row >> 4)) * ((size_t)K * 16) + lane * 8;
+    }
+
+    // ---- token tile staging: thread owns 16-byte chunk (tid % 8) of rows tid/8 + 32p ----
     const int chunk = tid & 7;
-    const bf16_t* wsrc[4];
     const bf16_t* xsrc[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int r = (tid >> 3) + 32 * p;
-        if (GATEUP) {
-            const bf16_t* base = (r < 64) ? w0 : w1;
-            wsrc[p] = base + ((size_t)ti.expert * features + f0 + (r & 63)) * K + chunk * 8;
-        } else {
-            wsrc[p] = w0 + ((size_t)ti.expert * features + f0 + r) * K + chunk * 8;
-        }
         const int rr = min(r, ti.rows - 1);  // rows past the group end re-read its last row; never stored
         const int src_row = row_token ? row_token[ti.row0 + rr] : ti.row0 + rr;
         xsrc[p] = in + (size_t)src_row * K + chunk * 8;
     }
-
-    u32x4_t wreg[4], xreg[4];
-    auto load_stage = [&](int kt) {
+    u32x4_t xreg[4];
+    auto load_x = [&](int kt) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            wreg[p] = *(const u32x4_t*)(wsrc[p] + kt * BK);
-            xreg[p] = *(const u32x4_t*)(xsrc[p] + kt * BK);
-        }
+        for (int p = 0; p < 4; ++p) xreg[p] = *(const u32x4_t*)(xsrc[p] + kt * BK);
     };
-    auto store_stage = [&](int buf) {
+    auto store_x = [&](int buf) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int r = (tid >> 3) + 32 * p;
-            *(u32x4_t*)(&lds_w[buf][r * LDS_LD + chunk * 8]) = wreg[p];
-            *(u32x4_t*)(&lds_x[buf][r * LDS_LD + chunk * 8]) = xreg[p];
-        }
+        for (int p = 0; p < 4; ++p)
+            *(u32x4_t*)(&lds_x[buf][((tid >> 3) + 32 * p) * LDS_LD + chunk * 8]) = xreg[p];
     };
 
-    f32x16_t acc[2][2];
+    f32x4_t acc[WB][TB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < WB; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < TB; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+            for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.0f;
 
-    // LDS rows of this wave's feature blocks and token blocks
-    int wrow[2], xrow[2];
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb) wrow[fb] = (GATEUP ? fb * 64 + wf * 32 : wf * 64 + fb * 32) + (lane & 31);
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) xrow[tb] = wt * 64 + tb * 32 + (lane & 31);
-    const int koff = (lane >> 5) * 8;
-
+    bf16x8_t areg[WB][KS];
     const int nk = K / BK;
-    load_stage(0);
-    store_stage(0);
+    load_x(0);
+#pragma unroll
+    for (int fb = 0; fb < WB; ++fb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) areg[fb][ks] = *(const bf16x8_t*)(aptr[fb] + ks * 512);
+    store_x(0);
     __syncthreads();
+
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < nk) load_stage(kt + 1);
+        const int kn = min(kt + 1, nk - 1);  // the last stage re-fetches itself: branch-free, in bounds, unused
+        load_x(kn);
+        __builtin_amdgcn_sched_barrier(0);  // keep the token-tile loads at the top: they are consumed after the MFMAs
+        // (waves of a ragged last column run the same loop on weight row 0: a branch here would make the compiler
+        //  shuttle all 256 accumulators between register files every iteration)
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t a[2], b[2];
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8_t b[TB];
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb) a[fb] = *(const bf16x8_t*)(&lds_w[buf][wrow[fb] * LDS_LD + ks * 16 + koff]);
+            for (int tb = 0; tb < TB; ++tb)
+                b[tb] = *(const bf16x8_t*)(&lds_x[buf][(tb * 16 + l16) * LDS_LD + ks * 32 + koff]);
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) b[tb] = *(const bf16x8_t*)(&lds_x[buf][xrow[tb] * LDS_LD + ks * 16 + koff]);
+            for (int fb = 0; fb < WB; ++fb)
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb)
+                for (int tb = 0; tb < TB; ++tb)
+                    acc[fb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[fb][ks], b[tb], acc[fb][tb], 0, 0, 0);
 #pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-                    acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[fb], b[tb], acc[fb][tb], 0, 0, 0);
+            for (int fb = 0; fb < WB; ++fb) areg[fb][ks] = *(const bf16x8_t*)(aptr[fb] + (size_t)(kn * KS + ks) * 512);
+            __builtin_amdgcn_sched_barrier(0);  // refill each fragment right after its last use, one k-step at a time
         }
-        if (kt + 1 < nk) store_stage(buf ^ 1);
+        store_x(buf ^ 1);
         __syncthreads();
     }
+    if (!active) return;
 
-    // ---- epilogue ----
+    // ---- epilogue: in a 16 x 16 accumulator block a lane owns token (lane % 16) and features 4*(lane/16) + 0..3
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        const int r = wt * 64 + tb * 32 + (lane & 31);
+    for (int tb = 0; tb < TB; ++tb) {
+        const int r = tb * 16 + l16;
         if (r >= ti.rows) continue;
         const size_t row = (size_t)(ti.row0 + r);
         if (GATEUP) {
-            bf16_t* o = (bf16_t*)out + row * features + f0 + wf * 32 + (lane >> 5) * 4;
+            bf16_t* o = (bf16_t*)out + row * features + wave_f0 + kq * 4;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
+            for (int fb = 0; fb < 2; ++fb) {
                 float v[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = silu(acc[0][tb][4 * g + i]) * acc[1][tb][4 * g + i];
+                for (int i = 0; i < 4; ++i) v[i] = silu(acc[fb][tb][i]) * acc[fb + 2][tb][i];
                 u32x2_t pk;
                 pk[0] = pack_bf16x2(v[0], v[1]);
                 pk[1] = pack_bf16x2(v[2], v[3]);
-                *(u32x2_t*)(o + 8 * g) = pk;
+                *(u32x2_t*)(o + 16 * fb) = pk;
             }
         } else {
+            float* o = (float*)out + row * features + wave_f0 + kq * 4;
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb) {
-                float* o = (float*)out + row * features + f0 + wf * 64 + fb * 32 + (lane >> 5) * 4;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    f32x4_t v;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = acc[fb][tb][4 * g + i];
-                    *(f32x4_t*)(o + 8 * g) = v;
-                }
-            }
+            for (int fb = 0; fb < WB; ++fb) *(f32x4_t*)(o + 16 * fb) = acc[fb][tb];
         }
     }
 }
@@ -182,26 +197,56 @@ ffn_f32_kernel(const float* __restrict__ in, const int32_t* __restrict__ row_tok
     if (!fetch_tile(sched, sched_count, blockIdx.y, M, tile_tokens, ti)) return;
     const int f = blockIdx.x * 256 + threadIdx.x;
     if (f >= features) return;
-    const float* wr0 = w0 + ((size_t)ti.expert * features + f) * K;
-    const float* wr1 = GATEUP ? w1 + ((size_t)ti.expert * features + f) * K : nullptr;
+    const float* wr0 = w0 + (size_t)ti.expert * features * K;
+    const float* wr1 = GATEUP ? w1 + (size_t)ti.expert * features * K : nullptr;
     for (int r = 0; r < ti.rows; ++r) {
         const int src_row = row_token ? row_token[ti.row0 + r] : ti.row0 + r;
         const float* xr = in + (size_t)src_row * K;
         float a0 = 0.0f, a1 = 0.0f;
         for (int j = 0; j < K; ++j) {
             const float xv = xr[j];
-            a0 = __builtin_fmaf(xv, wr0[j], a0);
-            if (GATEUP) a1 = __builtin_fmaf(xv, wr1[j], a1);
+            const size_t wi = packed_index(f, j, K);
+            a0 = __builtin_fmaf(xv, wr0[wi], a0);
+            if (GATEUP) a1 = __builtin_fmaf(xv, wr1[wi], a1);
         }
         out[(size_t)(ti.row0 + r) * features + f] = GATEUP ? silu(a0) * a1 : a0;
     }
+}
+
+// pack_kernel: row-major [n_mat][R][K] -> packed layout, one 16-byte (bf16) or 32-byte (fp32) run per thread.
+template <typename VEC>
+__global__ void __launch_bounds__(256)
+pack_kernel(const VEC* __restrict__ src, VEC* __restrict__ dst, int R, int K, size_t runs_total) {
+    const size_t run = (size_t)blockIdx.x * 256 + threadIdx.x;  // index of the destination run
+    if (run >= runs_total) return;
+    const size_t runs_per_mat = (size_t)R * (K >> 3);
+    const size_t mat = run / runs_per_mat;
+    const size_t in_mat = run % runs_per_mat;
+    const int i = (int)(in_mat & 15), q = (int)((in_mat >> 4) & 3);
+    const size_t blk = in_mat >> 6;
+    const int kb = (int)(blk % (size_t)(K >> 5)), rb = (int)(blk / (size_t)(K >> 5));
+    const int r = rb * 16 + i, k = kb * 32 + q * 8;
+    dst[run] = src[mat * runs_per_mat + ((size_t)r * K + k) / 8];
+}
+
+hipError_t launch_pack(const void* src, void* dst, int64_t n_mat, int R, int K, bool is_bf16, hipStream_t s) {
+    const size_t runs = (size_t)n_mat * R * (K >> 3);
+    if (runs == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((runs + 255) / 256);
+    if (is_bf16) {
+        hipLaunchKernelGGL(pack_kernel<u32x4_t>, dim3(blocks), dim3(256), 0, s, (const u32x4_t*)src, (u32x4_t*)dst, R, K, runs);
+    } else {
+        typedef __attribute__((ext_vector_type(8))) uint32_t u32x8_t;
+        hipLaunchKernelGGL(pack_kernel<u32x8_t>, dim3(blocks), dim3(256), 0, s, (const u32x8_t*)src, (u32x8_t*)dst, R, K, runs);
+    }
+    return hipGetLastError();
 }
 
 template <bool GATEUP>
 static hipError_t launch_ffn(const FfnArgs& a, hipStream_t s) {
     if (a.max_tiles <= 0) return hipSuccess;
     if (a.is_bf16) {
-        const dim3 grid(a.features / (GATEUP ? 64 : 128), a.max_tiles);
+        const dim3 grid((a.features + (GATEUP ? 127 : 255)) / (GATEUP ? 128 : 256), a.max_tiles);
         hipLaunchKernelGGL((ffn_mfma_kernel<GATEUP>), grid, dim3(256), 0, s, (const bf16_t*)a.in, a.row_token,
                            (const bf16_t*)a.w0, (const bf16_t*)a.w1, a.K, a.features, a.M, a.tile_tokens, a.sched,
                            a.sched_count, a.out);

@@ -37,7 +37,7 @@ struct FfnArgs {
     bool is_bf16;
     const void* in;            // row-major [*][K]
     const int32_t* row_token;  // gather map row -> input row, or null (identity)
-    const void* w0;            // gate (GATE/UP) or down weights, [E][features][K]
+    const void* w0;            // gate (GATE/UP) or down weights, [E] packed matrices of [features][K]
     const void* w1;            // up weights or null
     int K;                     // reduction length
     int features;              // F (gate/up) or d (down)
@@ -51,6 +51,9 @@ struct FfnArgs {
 
 hipError_t launch_gateup(const FfnArgs& a, hipStream_t s);
 hipError_t launch_down(const FfnArgs& a, hipStream_t s);
+
+// row-major [n_mat][R][K] -> packed expert-weight layout (R % 16 == 0, K % 32 == 0)
+hipError_t launch_pack(const void* src, void* dst, int64_t n_mat, int R, int K, bool is_bf16, hipStream_t s);
 
 struct CombineArgs {
     const float* y_slot;       // [T*k][d] fp32, permuted rows

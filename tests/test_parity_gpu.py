@@ -93,3 +93,22 @@ def test_stack_with_per_layer_k_vector():
     P.lexi_moe_layer_forward(dls[2], x[0].contiguous(), y3, int(kv[2]), ws)
     torch.cuda.synchronize()
     assert torch.equal(y2[0], y[0]) and torch.equal(y2[2], y3)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_pack_weights_matches_the_documented_index(dtype):
+    """lexi_pack_weights against the layout formula printed in the header, on matrices of distinct values."""
+    import torch
+    import paper_2509_02753_amd as P
+    n, R, K = 3, 48, 96
+    src = torch.arange(n * R * K, dtype=torch.float32).reshape(n, R, K) % 251   # exact in bf16
+    src = src.to(torch.bfloat16 if dtype == "bf16" else torch.float32).cuda().contiguous()
+    packed = P.lexi_pack_weights(src).float().cpu().numpy().reshape(n, R * K)
+    ref = src.float().cpu().numpy()
+    r, k = np.meshgrid(np.arange(R), np.arange(K), indexing="ij")
+    idx = ((((r // 16) * (K // 32) + k // 32) * 64 + ((k % 32) // 8) * 16 + r % 16) * 8 + k % 8)
+    assert np.array_equal(np.sort(idx.reshape(-1)), np.arange(R * K))           # the formula is a permutation
+    for m in range(n):
+        assert np.array_equal(packed[m][idx], ref[m])
+    with pytest.raises(P.LexiError):
+        P.lexi_pack_weights(torch.zeros((40, 96), dtype=torch.bfloat16, device="cuda"))   # rows % 16 != 0
