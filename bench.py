@@ -70,8 +70,11 @@ def main():
 
     log(f"[bench] {cfg.name} T={T} L={L} kvec={kvec.tolist()} (sum {int(kvec.sum())}, uniform {int(kuni.sum())})")
     t0 = time.time()
-    dev_tensors = [S.device_layer(cfg, l, dev) for l in range(L)]
-    layers = [P.Layer.from_tensors(t, shared_kind=cfg.shared_kind) for t in dev_tensors]
+    layers = []
+    for l in range(L):
+        row_major = S.device_layer(cfg, l, dev)          # seeded generator, straight into HBM
+        layers.append(P.Layer.from_tensors(row_major, shared_kind=cfg.shared_kind))   # packed by the library's kernel
+        del row_major
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     x = torch.empty((L, T, cfg.d), dtype=tdt, device=dev)
     for l in range(L):
@@ -144,7 +147,9 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle as O
-        n = args.cpu_sample_tokens or max(1, min(T, int(64 * (6 * 2048 * 1024 * 6) / (float(np.mean(kvec)) * 6 * cfg.d * cfg.F + 6 * cfg.d * cfg.F_shared))))
+        # about 15 s of oracle work on 16 cores: the oracle does ~1 GFLOP/s per core on the FFN loops
+        per_token = sum(int(k) * 6.0 * cfg.d * cfg.F + 6.0 * cfg.d * cfg.F_shared + 2.0 * cfg.d * cfg.E for k in kvec)
+        n = args.cpu_sample_tokens or max(1, min(T, int(15.0 * 16e9 / per_token)))
 
         def to_host_layer(tensors):
             """Device tensors of one layer -> numpy (bf16 as uint16 bit patterns); the inputs, copied D2H."""
@@ -160,7 +165,7 @@ def main():
 
         wall = 0.0
         for l in range(L):
-            hl = O.Layer.from_tensors(cfg, to_host_layer(dev_tensors[l]))
+            hl = O.Layer.from_tensors(cfg, to_host_layer(S.device_layer(cfg, l, dev)))  # same seeded tensors, row-major
             xh = x[l, :n].contiguous()
             xh = xh.view(torch.int16).cpu().numpy().view(np.uint16) if tdt == torch.bfloat16 else xh.cpu().numpy()
             t1 = time.perf_counter()

@@ -57,6 +57,8 @@ __device__ __forceinline__ bool fetch_tile(const int32_t* sched, const int32_t* 
 //   Token rows are gathered through row_token (no permuted copy of X is ever materialised).
 //   Waves whose feature range lies past `features` (ragged last workgroup column) only help staging the tokens.
 // ---------------------------------------------------------------------------------------------------------
+template <int S> struct StageTag { static constexpr int value = S; };
+
 template <bool GATEUP>
 __global__ void __launch_bounds__(256, 2)
 ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_token, const bf16_t* __restrict__ w0,
@@ -132,30 +134,44 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
     store_x(0);
     __syncthreads();
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        const int kn = min(kt + 1, nk - 1);  // the last stage re-fetches itself: branch-free, in bounds, unused
-        load_x(kn);
-        __builtin_amdgcn_sched_barrier(0);  // keep the token-tile loads at the top: they are consumed after the MFMAs
-        // (waves of a ragged last column run the same loop on weight row 0: a branch here would make the compiler
-        //  shuttle all 256 accumulators between register files every iteration)
+    // The K loop, specialised on the number of 16-token blocks the tile really holds: the last tile of an expert's
+    // group (and every tile of a decode-sized batch) skips the MFMAs of token blocks that would only hold padding.
+    auto k_loop = [&](auto ntb_tag) {
+        constexpr int NTB = decltype(ntb_tag)::value;
+        for (int kt = 0; kt < nk; ++kt) {
+            const int buf = kt & 1;
+            const int kn = min(kt + 1, nk - 1);  // the last stage re-fetches itself: branch-free, in bounds, unused
+            load_x(kn);
+            __builtin_amdgcn_sched_barrier(0);  // keep the token-tile loads at the top: they are consumed after the MFMAs
+            // (waves of a ragged last column run the same loop on weight row 0 instead of branching around it)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bf16x8_t b[TB];
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8_t b[NTB];
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb)
-                b[tb] = *(const bf16x8_t*)(&lds_x[buf][(tb * 16 + l16) * LDS_LD + ks * 32 + koff]);
+                for (int tb = 0; tb < NTB; ++tb)
+                    b[tb] = *(const bf16x8_t*)(&lds_x[buf][(tb * 16 + l16) * LDS_LD + ks * 32 + koff]);
 #pragma unroll
-            for (int fb = 0; fb < WB; ++fb)
+                for (int fb = 0; fb < WB; ++fb)
 #pragma unroll
-                for (int tb = 0; tb < TB; ++tb)
-                    acc[fb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[fb][ks], b[tb], acc[fb][tb], 0, 0, 0);
+                    for (int tb = 0; tb < NTB; ++tb)
+                        acc[fb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[fb][ks], b[tb], acc[fb][tb], 0, 0, 0);
 #pragma unroll
-            for (int fb = 0; fb < WB; ++fb) areg[fb][ks] = *(const bf16x8_t*)(aptr[fb] + (size_t)(kn * KS + ks) * 512);
-            __builtin_amdgcn_sched_barrier(0);  // refill each fragment right after its last use, one k-step at a time
+                for (int fb = 0; fb < WB; ++fb) areg[fb][ks] = *(const bf16x8_t*)(aptr[fb] + (size_t)(kn * KS + ks) * 512);
+                __builtin_amdgcn_sched_barrier(0);  // refill each fragment right after its last use, one k-step at a time
+            }
+            store_x(buf ^ 1);
+            __syncthreads();
         }
-        store_x(buf ^ 1);
-        __syncthreads();
+    };
+    switch ((ti.rows + 15) >> 4) {
+        case 1: k_loop(StageTag<1>{}); break;
+        case 2: k_loop(StageTag<2>{}); break;
+        case 3: k_loop(StageTag<3>{}); break;
+        case 4: k_loop(StageTag<4>{}); break;
+        case 5: k_loop(StageTag<5>{}); break;
+        case 6: k_loop(StageTag<6>{}); break;
+        case 7: k_loop(StageTag<7>{}); break;
+        default: k_loop(StageTag<8>{}); break;
     }
     if (!active) return;
 
