@@ -8,6 +8,8 @@ namespace {
 using namespace lexi;
 
 constexpr int kTileTokens = 128;  // token-tile height of the grouped GEMM kernels
+constexpr int kStreamRowsPerExpert = 2;   // mean rows per expert at or below which the routed FFN streams weights
+constexpr int kStreamDenseRows = 64;      // token count at or below which the shared expert streams weights
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -39,7 +41,8 @@ Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
     const size_t A = (size_t)T * k;
     const size_t es = ly.dtype == LEXI_BF16 ? 2 : 4;
     const size_t nblk = ((size_t)T + 7) / 8;  // router blocks never hold fewer than 8 tokens
-    w.max_tiles = (int)((A + kTileTokens - 1) / kTileTokens) + ly.E;
+    // every expert with rows has one ragged tile at most, the rest are full
+    w.max_tiles = (int)(A / kTileTokens) + (int)(A < (size_t)ly.E ? A : (size_t)ly.E);
     w.partial = c.take<float>((size_t)(ly.d / 128) * T * 64);
     w.topk_idx = c.take<int32_t>(A);
     w.gates = c.take<float>(A);
@@ -133,7 +136,11 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     if (launch_routing(r, s) != hipSuccess) return LEXI_ERR_LAUNCH;
     mark(1);
 
+    // few rows per expert (decode): the weight-streaming schedule; otherwise the MFMA tile schedule
+    const bool stream_routed = (int64_t)T * k <= (int64_t)kStreamRowsPerExpert * ly.E;
+    const bool stream_shared = T <= kStreamDenseRows;
     FfnArgs g{};
+    g.streaming = stream_routed;
     g.is_bf16 = bf; g.in = x; g.row_token = w.row_token; g.w0 = ly.w_gate; g.w1 = ly.w_up; g.K = ly.d;
     g.features = ly.F; g.M = T * k; g.max_tiles = w.max_tiles; g.tile_tokens = kTileTokens; g.sched = w.sched;
     g.sched_count = w.sched_count; g.out = w.act;
@@ -141,6 +148,7 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     mark(2);
 
     FfnArgs dn{};
+    dn.streaming = stream_routed;
     dn.is_bf16 = bf; dn.in = w.act; dn.row_token = nullptr; dn.w0 = ly.w_down; dn.w1 = nullptr; dn.K = ly.F;
     dn.features = ly.d; dn.M = T * k; dn.max_tiles = w.max_tiles; dn.tile_tokens = kTileTokens; dn.sched = w.sched;
     dn.sched_count = w.sched_count; dn.out = w.y_slot;
@@ -150,11 +158,13 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     if (ly.F_shared > 0) {
         const int dense_tiles = (T + kTileTokens - 1) / kTileTokens;
         FfnArgs sg{};
+        sg.streaming = stream_shared;
         sg.is_bf16 = bf; sg.in = x; sg.row_token = nullptr; sg.w0 = ly.ws_gate; sg.w1 = ly.ws_up; sg.K = ly.d;
         sg.features = ly.F_shared; sg.M = T; sg.max_tiles = dense_tiles; sg.tile_tokens = kTileTokens;
         sg.sched = nullptr; sg.sched_count = nullptr; sg.out = w.act_shared;
         if (launch_gateup(sg, s) != hipSuccess) return LEXI_ERR_LAUNCH;
         FfnArgs sd{};
+        sd.streaming = stream_shared;
         sd.is_bf16 = bf; sd.in = w.act_shared; sd.row_token = nullptr; sd.w0 = ly.ws_down; sd.w1 = nullptr;
         sd.K = ly.F_shared; sd.features = ly.d; sd.M = T; sd.max_tiles = dense_tiles; sd.tile_tokens = kTileTokens;
         sd.sched = nullptr; sd.sched_count = nullptr; sd.out = w.y_shared;

@@ -35,6 +35,7 @@ hipError_t launch_routing(const RoutingArgs& a, hipStream_t s);
 // == null: one group of M rows, expert 0).
 struct FfnArgs {
     bool is_bf16;
+    bool streaming;            // few rows per expert: use the weight-streaming (HBM-bound) schedule
     const void* in;            // row-major [*][K]
     const int32_t* row_token;  // gather map row -> input row, or null (identity)
     const void* w0;            // gate (GATE/UP) or down weights, [E] packed matrices of [features][K]
