@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--kvec", default="lexi", choices=["lexi", "uniform"])
     ap.add_argument("--layers", type=int, default=None, help="use only the first N layers (debugging; not a valid result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-uniform", action="store_true", help="skip the uniform-k comparison run (profiling: every launch then uses k_vec)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -102,8 +103,9 @@ def main():
 
     sec = timed(kvec)
     log(f"[bench] k={args.kvec}: {sec * 1e3:.3f} ms/step, {T / sec:,.0f} tokens/s")
-    sec_uniform = timed(kuni) if args.kvec == "lexi" else sec
-    if args.kvec == "lexi":
+    compare_uniform = args.kvec == "lexi" and not args.no_uniform
+    sec_uniform = timed(kuni) if compare_uniform else None
+    if compare_uniform:
         log(f"[bench] uniform k={cfg.k_base}: {sec_uniform * 1e3:.3f} ms/step, {T / sec_uniform:,.0f} tokens/s")
 
     # ---- per-stage durations with HIP events recorded by the library on the launch stream ----
@@ -183,8 +185,8 @@ def main():
         "config": {"workload": f"{cfg.name} L={L} d={cfg.d} E={cfg.E} F={cfg.F} Fs={cfg.F_shared} T={T}",
                    "k_vec": kvec.tolist(), "k_sum": int(kvec.sum()), "k_uniform": int(cfg.k_base),
                    "regime": "prefill" if prefill else "decode"},
-        "uniform_k_tokens_per_s": round(T / sec_uniform, 1),
-        "speedup_vs_uniform_k": round(sec_uniform / sec, 4),
+        "uniform_k_tokens_per_s": round(T / sec_uniform, 1) if sec_uniform else None,
+        "speedup_vs_uniform_k": round(sec_uniform / sec, 4) if sec_uniform else None,
         "stage_ms_per_step": {n: round(float(v), 4) for n, v in zip(P.STAGE_NAMES, per_stage)},
         "roofline": roofline, "whole_path": whole, "cpu_baseline": cpu,
     }

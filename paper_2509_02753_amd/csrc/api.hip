@@ -29,7 +29,7 @@ struct Carver {
 
 struct Workspace {
     int32_t *topk_idx, *local_rank, *blk_hist, *counts, *offsets, *perm, *inv_perm, *row_token, *sched, *sched_count;
-    float *gates, *partial, *y_slot, *y_shared, *coef;
+    float *gates, *partial, *y_slot, *y_shared;
     void *act, *act_shared;
     int max_tiles;
     size_t bytes;
@@ -60,7 +60,6 @@ Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
     if (ly.F_shared > 0) {
         w.act_shared = c.take<char>((size_t)T * ly.F_shared * es);
         w.y_shared = c.take<float>((size_t)T * ly.d);
-        w.coef = c.take<float>((size_t)T);
     }
     w.bytes = align_up(c.used, 256);
     return w;
@@ -169,9 +168,6 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
         sd.K = ly.F_shared; sd.features = ly.d; sd.M = T; sd.max_tiles = dense_tiles; sd.tile_tokens = kTileTokens;
         sd.sched = nullptr; sd.sched_count = nullptr; sd.out = w.y_shared;
         if (launch_down(sd, s) != hipSuccess) return LEXI_ERR_LAUNCH;
-        if (ly.shared_kind == LEXI_SHARED_SIGMOID &&
-            launch_shared_gate(x, ly.w_shared_gate, bf, T, ly.d, w.coef, s) != hipSuccess)
-            return LEXI_ERR_LAUNCH;
     }
 
     mark(4);
@@ -179,7 +175,8 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     CombineArgs c{};
     c.y_slot = w.y_slot; c.inv_perm = w.inv_perm; c.gates = w.gates;
     c.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr;
-    c.shared_coef = ly.shared_kind == LEXI_SHARED_SIGMOID ? w.coef : nullptr;
+    c.x = x; c.x_bf16 = bf;
+    c.w_shared_gate = ly.shared_kind == LEXI_SHARED_SIGMOID ? ly.w_shared_gate : nullptr;
     c.T = T; c.d = ly.d; c.k = k; c.y = y; c.y_bf16 = y_dtype == LEXI_BF16;
     if (launch_combine(c, s) != hipSuccess) return LEXI_ERR_LAUNCH;
     mark(5);

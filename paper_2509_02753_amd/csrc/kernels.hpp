@@ -61,14 +61,13 @@ struct CombineArgs {
     const int32_t* inv_perm;   // [T*k]
     const float* gates;        // [T*k]
     const float* y_shared;     // [T][d] fp32 or null
-    const float* shared_coef;  // [T] or null (= 1)
+    const void* x;             // [T][d] layer input (only read for a sigmoid-gated shared expert)
+    const void* w_shared_gate; // [d] or null (ungated: coefficient 1)
+    bool x_bf16;
     int T, d, k;
     void* y;                   // [T][d]
     bool y_bf16;
 };
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
-
-// coef[t] = sigmoid(x[t] . w)   (the gate in front of a sigmoid-gated shared expert)
-hipError_t launch_shared_gate(const void* x, const void* w, bool is_bf16, int T, int d, float* coef, hipStream_t s);
 
 }  // namespace lexi

@@ -170,6 +170,7 @@ topk_kernel(const float* __restrict__ partial, const float* __restrict__ bias, i
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int tok0 = blockIdx.x * TB + wave * TM;
+    const int tok_end = T;
 
     float total[TM];
 #pragma unroll
@@ -177,11 +178,25 @@ topk_kernel(const float* __restrict__ partial, const float* __restrict__ bias, i
         const int t = min(tok0 + m, T - 1);
         total[m] = partial[(size_t)t * 64 + lane];
     }
-    for (int sg = 1; sg < nseg; ++sg) {
+    // ordered sum of the remaining partials; the loads of CH segments are issued together (the adds stay in order)
+    constexpr int CH = 8;
+    for (int sg0 = 1; sg0 < nseg; sg0 += CH) {
+        float tmp[CH][TM];
 #pragma unroll
-        for (int m = 0; m < TM; ++m) {
-            const int t = min(tok0 + m, T - 1);
-            total[m] = total[m] + partial[((size_t)sg * T + t) * 64 + lane];
+        for (int c = 0; c < CH; ++c) {
+            const int sg = min(sg0 + c, nseg - 1);
+#pragma unroll
+            for (int m = 0; m < TM; ++m) {
+                const int t = min(tok0 + m, T - 1);
+                tmp[c][m] = partial[((size_t)sg * T + t) * 64 + lane];
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            if (sg0 + c < nseg) {
+#pragma unroll
+                for (int m = 0; m < TM; ++m) total[m] = total[m] + tmp[c][m];
+            }
         }
     }
     const bool lane_valid = lane < E;
@@ -191,32 +206,41 @@ topk_kernel(const float* __restrict__ partial, const float* __restrict__ bias, i
         for (int m = 0; m < TM; ++m) total[m] = total[m] + b;
     }
 
-    int32_t cnt = 0;           // lane e: assignments to expert e made so far by this wave
-    int32_t sel[TM], rnk[TM];  // lane s (< k): expert, gate and rank-in-wave of slot s of token m
+    // ---- top-k: slot-major, token-minor, so the TM independent reduction chains of one round overlap ----
+    uint32_t taken = 0;        // lane e: bit m set once token m has selected expert e
+    int32_t sel[TM];           // lane s (< k): expert in slot s of token m
+    float val[TM];             // lane s (< k): its logit
+#pragma unroll
+    for (int m = 0; m < TM; ++m) { sel[m] = 0; val[m] = -INFINITY; }
+    for (int s = 0; s < k; ++s) {
+#pragma unroll
+        for (int m = 0; m < TM; ++m) {
+            if (tok0 + m < tok_end) {  // wave-uniform: rows past the wave's range are skipped
+                const bool open = lane_valid && !((taken >> m) & 1u);
+                const float mx = wave_max(open ? total[m] : -INFINITY);
+                const uint64_t holders = __ballot(open && total[m] == mx);
+                const int e_star = __builtin_ctzll(holders);  // lowest index among equal logits
+                if (lane == e_star) taken |= 1u << m;
+                if (lane == s) { sel[m] = e_star; val[m] = mx; }
+            }
+        }
+    }
+    // ---- gates: softmax over the selected logits; slot 0 holds the largest ----
     float gte[TM];
 #pragma unroll
     for (int m = 0; m < TM; ++m) {
-        float l = lane_valid ? total[m] : -INFINITY;
-        bool taken = !lane_valid;
-        const int32_t counted = (tok0 + m < T) ? 1 : 0;  // tail rows past T must not enter the histogram
-        int32_t my_sel = 0, my_rank = 0;
-        float my_val = -INFINITY;
-        for (int s = 0; s < k; ++s) {
-            const float cand = taken ? -INFINITY : l;
-            const float mx = wave_max(cand);
-            const uint64_t holders = __ballot(!taken && l == mx);
-            const int e_star = __builtin_ctzll(holders);  // lowest index among equal logits
-            const int32_t r = __builtin_amdgcn_readlane(cnt, e_star);
-            if (lane == e_star) { taken = true; cnt += counted; }
-            if (lane == s) { my_sel = e_star; my_val = mx; my_rank = r; }
-        }
-        // softmax over the selected logits; slot 0 holds the largest
-        const float v0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_val), 0));
-        const float ex = (lane < k) ? __expf(my_val - v0) : 0.0f;
-        const float denom = wave_sum(ex);
-        sel[m] = my_sel;
-        rnk[m] = my_rank;
-        gte[m] = ex / denom;
+        const float v0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(val[m]), 0));
+        const float ex = (lane < k) ? __expf(val[m] - v0) : 0.0f;
+        gte[m] = ex / wave_sum(ex);
+    }
+    // ---- rank of each assignment among this wave's earlier assignments to the same expert (tokens ascending):
+    //      lane e counts its own expert's hits in token order, the slot lanes fetch theirs with one permute ----
+    int32_t cnt = 0;
+    int32_t rnk[TM];
+#pragma unroll
+    for (int m = 0; m < TM; ++m) {
+        rnk[m] = __builtin_amdgcn_ds_bpermute(sel[m] << 2, cnt);
+        cnt += (int32_t)((taken >> m) & 1u);
     }
 
     wave_cnt[wave][lane] = cnt;
