@@ -35,12 +35,13 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
     __shared__ __attribute__((aligned(16))) bf16_t lds_x[2][TT * LDS_LD];
 
     TileInfo ti;
-    if (!fetch_tile(sched, sched_count, blockIdx.y, M, tile_tokens, ti)) return;
+    int cb;
+    if (!fetch_item(sched, sched_count, (features + (GATEUP ? 127 : 255)) / (GATEUP ? 128 : 256), M, tile_tokens, ti, cb)) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wave_f0 = blockIdx.x * (GATEUP ? 128 : 256) + wave * (GATEUP ? 32 : 64);  // first output feature
+    const int wave_f0 = cb * (GATEUP ? 128 : 256) + wave * (GATEUP ? 32 : 64);  // first output feature
     const bool active = wave_f0 < features;
     const int l16 = lane & 15, kq = lane >> 4;
     const int koff = kq * 8;
@@ -230,7 +231,8 @@ static hipError_t launch_ffn(const FfnArgs& a, hipStream_t s) {
     if (a.max_tiles <= 0) return hipSuccess;
     if (a.is_bf16 && a.streaming) return GATEUP ? launch_gateup_stream(a, s) : launch_down_stream(a, s);
     if (a.is_bf16) {
-        const dim3 grid((a.features + (GATEUP ? 127 : 255)) / (GATEUP ? 128 : 256), a.max_tiles);
+        const int ncb = (a.features + (GATEUP ? 127 : 255)) / (GATEUP ? 128 : 256);
+        const dim3 grid(xcd_grid(ncb, a.max_tiles));
         hipLaunchKernelGGL((ffn_mfma_kernel<GATEUP>), grid, dim3(256), 0, s, (const bf16_t*)a.in, a.row_token,
                            (const bf16_t*)a.w0, (const bf16_t*)a.w1, a.K, a.features, a.M, a.tile_tokens, a.sched,
                            a.sched_count, a.out);

@@ -314,8 +314,9 @@ scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, in
             s[0] = lane;                     // expert
             s[1] = off + i * tile_tokens;    // first permuted row
             s[2] = rows;                     // valid rows in this tile
-            s[3] = 0;
+            s[3] = i;                        // index of the tile inside its expert
         }
+        sched_count[4 + lane] = ntile;       // tiles of this expert
     }
     if (lane == 63) {
         // lanes >= E carry zero counts, so lane 63's exclusive sums plus its own are the totals
