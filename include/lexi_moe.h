@@ -17,7 +17,12 @@
  *     lexi_layer_t / lexi_routing_out_t structs themselves, and k_vec, live in
  *     HOST memory.  The library never allocates, frees or keeps a pointer.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL
- *     = the default stream) and the call returns without synchronising.
+ *     = the default stream) and the call returns without synchronising.  For
+ *     batches of at most 1024 tokens the shared expert's kernels run on a
+ *     library-owned side stream that forks from `hip_stream` at the start of
+ *     the layer and joins it again before the combine (events, no host
+ *     synchronisation): the caller sees plain stream semantics.  That stream
+ *     and its two events are created once per device, on first use.
  *   - On error a negative lexi_status is returned and nothing is launched.
  *   - Same inputs give the same output bits on every call; no call leaves
  *     state behind (k=2 then k=8 gives the k=8 result of a fresh call).

@@ -2,6 +2,7 @@
 // Nothing here allocates, synchronises or copies to the host; every launch goes to the caller's stream.
 #include "../../include/lexi_moe.h"
 #include "kernels.hpp"
+#include <mutex>
 
 namespace {
 
@@ -12,6 +13,35 @@ constexpr int kStreamRowsPerExpert = 2;   // mean rows per expert at or below wh
 constexpr int kStreamDenseRows = 64;      // token count at or below which the shared expert streams weights
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// The shared expert depends on x only, not on the routing, so for decode-sized batches (where its kernels are short
+// and latency-bound) it runs on a side stream that forks from the caller's stream at the start of the layer and joins
+// it again in front of the combine.  One side stream and one event pair per device, created on first use and kept
+// until the process ends; the caller sees plain stream semantics (and a capture of the caller's stream picks the
+// side stream up through the events).
+constexpr int kSideStreamMaxT = 1024;
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool tried = false, ok = false;
+};
+constexpr int kMaxDevices = 16;
+SideStream g_side[kMaxDevices];
+std::mutex g_side_mutex, g_side_enqueue_mutex;
+
+SideStream* side_stream() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideStream& ss = g_side[dev];
+    if (!ss.tried) {
+        ss.tried = true;
+        ss.ok = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess;
+    }
+    return ss.ok ? &ss : nullptr;   // no side stream: the shared expert simply stays on the caller's stream
+}
 
 // Walks the workspace once; with base == nullptr it only measures.
 struct Carver {
@@ -126,6 +156,33 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
         if (dbg->inv_perm) w.inv_perm = dbg->inv_perm;
     }
 
+    auto run_shared = [&](hipStream_t st) -> bool {
+        const int dense_tiles = (T + kTileTokens - 1) / kTileTokens;
+        const bool stream_shared = T <= kStreamDenseRows;
+        FfnArgs sg{};
+        sg.streaming = stream_shared;
+        sg.is_bf16 = bf; sg.in = x; sg.row_token = nullptr; sg.w0 = ly.ws_gate; sg.w1 = ly.ws_up; sg.K = ly.d;
+        sg.features = ly.F_shared; sg.M = T; sg.max_tiles = dense_tiles; sg.tile_tokens = kTileTokens;
+        sg.sched = nullptr; sg.sched_count = nullptr; sg.out = w.act_shared;
+        if (launch_gateup(sg, st) != hipSuccess) return false;
+        FfnArgs sd{};
+        sd.streaming = stream_shared;
+        sd.is_bf16 = bf; sd.in = w.act_shared; sd.row_token = nullptr; sd.w0 = ly.ws_down; sd.w1 = nullptr;
+        sd.K = ly.F_shared; sd.features = ly.d; sd.M = T; sd.max_tiles = dense_tiles; sd.tile_tokens = kTileTokens;
+        sd.sched = nullptr; sd.sched_count = nullptr; sd.out = w.y_shared;
+        return launch_down(sd, st) == hipSuccess;
+    };
+    SideStream* side = (ly.F_shared > 0 && T <= kSideStreamMaxT) ? side_stream() : nullptr;
+    // the fork/join events are shared by every call on the device: host threads enqueue their layers one at a time
+    std::unique_lock<std::mutex> side_lock(g_side_enqueue_mutex, std::defer_lock);
+    if (side) {
+        side_lock.lock();
+        if (hipEventRecord(side->fork, s) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+            return LEXI_ERR_LAUNCH;
+        if (!run_shared(side->stream)) return LEXI_ERR_LAUNCH;
+        if (hipEventRecord(side->join, side->stream) != hipSuccess) return LEXI_ERR_LAUNCH;
+    }
+
     RoutingArgs r{};
     r.x = x; r.is_bf16 = bf; r.w_router = ly.w_router; r.bias = ly.router_bias;
     r.T = T; r.d = ly.d; r.E = ly.E; r.k = k; r.tile_tokens = kTileTokens;
@@ -137,7 +194,6 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
 
     // few rows per expert (decode): the weight-streaming schedule; otherwise the MFMA tile schedule
     const bool stream_routed = (int64_t)T * k <= (int64_t)kStreamRowsPerExpert * ly.E;
-    const bool stream_shared = T <= kStreamDenseRows;
     FfnArgs g{};
     g.streaming = stream_routed;
     g.is_bf16 = bf; g.in = x; g.row_token = w.row_token; g.w0 = ly.w_gate; g.w1 = ly.w_up; g.K = ly.d;
@@ -155,21 +211,12 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     mark(3);
 
     if (ly.F_shared > 0) {
-        const int dense_tiles = (T + kTileTokens - 1) / kTileTokens;
-        FfnArgs sg{};
-        sg.streaming = stream_shared;
-        sg.is_bf16 = bf; sg.in = x; sg.row_token = nullptr; sg.w0 = ly.ws_gate; sg.w1 = ly.ws_up; sg.K = ly.d;
-        sg.features = ly.F_shared; sg.M = T; sg.max_tiles = dense_tiles; sg.tile_tokens = kTileTokens;
-        sg.sched = nullptr; sg.sched_count = nullptr; sg.out = w.act_shared;
-        if (launch_gateup(sg, s) != hipSuccess) return LEXI_ERR_LAUNCH;
-        FfnArgs sd{};
-        sd.streaming = stream_shared;
-        sd.is_bf16 = bf; sd.in = w.act_shared; sd.row_token = nullptr; sd.w0 = ly.ws_down; sd.w1 = nullptr;
-        sd.K = ly.F_shared; sd.features = ly.d; sd.M = T; sd.max_tiles = dense_tiles; sd.tile_tokens = kTileTokens;
-        sd.sched = nullptr; sd.sched_count = nullptr; sd.out = w.y_shared;
-        if (launch_down(sd, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+        if (side) {
+            if (hipStreamWaitEvent(s, side->join, 0) != hipSuccess) return LEXI_ERR_LAUNCH;
+        } else if (!run_shared(s)) {
+            return LEXI_ERR_LAUNCH;
+        }
     }
-
     mark(4);
 
     CombineArgs c{};
