@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uniform", action="store_true", help="skip the uniform-k comparison run (profiling: every launch then uses k_vec)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
+    ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
+                    help="replay the stack call from a captured HIP graph (auto: for decode-sized batches, whose steps are launch-bound)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -93,11 +95,30 @@ def main():
         for _ in range(n):
             P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr, stage_events=events)
 
+    prefill = (T * float(np.mean(kvec)) / cfg.E) >= 64
+    use_graph = args.graph == "on" or (args.graph == "auto" and not prefill)
+
+    def captured(kv):
+        """The whole stack call (every launch of all L layers, the side-stream fork/join included) as one HIP graph."""
+        run_steps(kv, 1)                       # first-use set-up inside the library happens outside the capture
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr)
+        return g
+
     def timed(kv):
-        run_steps(kv, args.warmup)
+        if use_graph:
+            g = captured(kv)
+            step = g.replay
+        else:
+            step = lambda: run_steps(kv, 1)
+        for _ in range(args.warmup):
+            step()
         torch.cuda.synchronize()
         t_start = time.perf_counter()
-        run_steps(kv, args.steps)
+        for _ in range(args.steps):
+            step()
         torch.cuda.synchronize()
         return (time.perf_counter() - t_start) / args.steps
 
@@ -128,7 +149,6 @@ def main():
     gu_flops, gu_bytes, tot_flops, tot_bytes = stage_flops_bytes(cfg, T, kvec, counts)
 
     gu_ms_avg = float(stage_ms[:, 1].mean())      # average duration of one gate/up launch
-    prefill = (T * float(np.mean(kvec)) / cfg.E) >= 64
     if prefill:
         achieved = gu_flops / L / (gu_ms_avg * 1e-3) / 1e12
         roofline = {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "mfma", "achieved": round(achieved, 2),
@@ -184,7 +204,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name} L={L} d={cfg.d} E={cfg.E} F={cfg.F} Fs={cfg.F_shared} T={T}",
                    "k_vec": kvec.tolist(), "k_sum": int(kvec.sum()), "k_uniform": int(cfg.k_base),
-                   "regime": "prefill" if prefill else "decode"},
+                   "regime": "prefill" if prefill else "decode", "hip_graph": bool(use_graph)},
         "uniform_k_tokens_per_s": round(T / sec_uniform, 1) if sec_uniform else None,
         "speedup_vs_uniform_k": round(sec_uniform / sec, 4) if sec_uniform else None,
         "stage_ms_per_step": {n: round(float(v), 4) for n, v in zip(P.STAGE_NAMES, per_stage)},

@@ -112,3 +112,34 @@ def test_pack_weights_matches_the_documented_index(dtype):
         assert np.array_equal(packed[m][idx], ref[m])
     with pytest.raises(P.LexiError):
         P.lexi_pack_weights(torch.zeros((40, 96), dtype=torch.bfloat16, device="cuda"))   # rows % 16 != 0
+
+
+def test_stack_replayed_from_a_hip_graph_matches_eager():
+    """A captured stack call (side-stream fork/join of the shared expert included) replays to the eager result,
+    every time, with eager work and synchronisations between the replays."""
+    import torch
+    import paper_2509_02753_amd as P
+    cfg = S.mini(S.C3, L=3, d=256, F=384)   # sigmoid-gated shared expert: the side stream is in the capture
+    T = 40
+    kv = cfg.k_lexi()
+    dls = [device_and_host_layer(cfg, l)[0] for l in range(cfg.L)]
+    x = torch.stack([S.device_x(cfg, l, T) for l in range(cfg.L)])
+    y_eager = torch.empty((cfg.L, T, cfg.d), dtype=torch.float32, device="cuda:0")
+    y_graph = torch.empty_like(y_eager)
+    ws = P.alloc_workspace(dls, T, int(kv.max()))
+    ws2 = P.alloc_workspace(dls, T, int(kv.max()))
+    P.lexi_moe_stack_forward(dls, kv, x, y_eager, ws)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        P.lexi_moe_stack_forward(dls, kv, x, y_graph, ws2)
+    for i in range(4):
+        y_graph.fill_(float("nan"))
+        ws2.fill_(0xFF)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), f"replay {i} differs from the eager result"
+        y_other = torch.empty_like(y_eager)
+        P.lexi_moe_stack_forward(dls, kv, x, y_other, ws)     # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(y_other, y_eager)
