@@ -127,8 +127,9 @@ router_partial_small_kernel(const void* __restrict__ x, const float* __restrict_
     const int t0 = blockIdx.y * TW;
     const int j_seg = seg * kRouterSegment;
     float w[kRouterSegment];
+    const float* wp = w_router + (size_t)j_seg * E + min(lane, E - 1);   // lanes >= E read a valid column; never used
 #pragma unroll
-    for (int jj = 0; jj < kRouterSegment; ++jj) w[jj] = (lane < E) ? w_router[(size_t)(j_seg + jj) * E + lane] : 0.0f;
+    for (int jj = 0; jj < kRouterSegment; ++jj) w[jj] = wp[(size_t)jj * E];
     for (int m = 0; m < TW; ++m) {
         const int t = t0 + m;
         if (t >= T) break;
@@ -270,12 +271,19 @@ topk_kernel(const float* __restrict__ partial, const float* __restrict__ bias, i
 // counts, offsets, and the token-tile schedule of the grouped GEMMs: tile i -> (expert, first row, rows).
 // Wave w scans its contiguous chunk of blocks, the chunk totals are combined through LDS.
 // ---------------------------------------------------------------------------------------------------------
+// With FUSE_PERMUTE (decode-sized batches) the same workgroup then scatters the assignments (the body of
+// permute_kernel), which saves a launch on the latency-bound path.
+template <bool FUSE_PERMUTE>
 __global__ void __launch_bounds__(1024)
 scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, int32_t* __restrict__ counts,
-            int32_t* __restrict__ offsets, int32_t* __restrict__ sched, int32_t* __restrict__ sched_count) {
+            int32_t* __restrict__ offsets, int32_t* __restrict__ sched, int32_t* __restrict__ sched_count,
+            const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ local_rank, int A, int k,
+            int tokens_per_block, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+            int32_t* __restrict__ row_token) {
     __shared__ int32_t chunk_tot[16][64];
     __shared__ int32_t s_cnt[64];
     __shared__ int32_t s_tiles[64];
+    __shared__ int32_t s_off[64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int chunk = (nblk + 15) / 16;
     const int b0 = wave * chunk, b1 = min(nblk, b0 + chunk);
@@ -302,26 +310,39 @@ scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, in
         s_tiles[lane] = ntile;
     }
     __syncthreads();
-    if (wave != 0) return;
-    int32_t off = 0, tile_base = 0;
-    for (int e = 0; e < lane; ++e) { off += s_cnt[e]; tile_base += s_tiles[e]; }
-    if (lane < E) {
-        counts[lane] = total;
-        offsets[lane] = off;
-        for (int i = 0; i < ntile; ++i) {
-            const int32_t rows = min(tile_tokens, total - i * tile_tokens);
-            int32_t* s = sched + (size_t)(tile_base + i) * 4;
-            s[0] = lane;                     // expert
-            s[1] = off + i * tile_tokens;    // first permuted row
-            s[2] = rows;                     // valid rows in this tile
-            s[3] = i;                        // index of the tile inside its expert
+    if (wave == 0) {
+        int32_t off = 0, tile_base = 0;
+        for (int e = 0; e < lane; ++e) { off += s_cnt[e]; tile_base += s_tiles[e]; }
+        s_off[lane] = off;
+        if (lane < E) {
+            counts[lane] = total;
+            offsets[lane] = off;
+            for (int i = 0; i < ntile; ++i) {
+                const int32_t rows = min(tile_tokens, total - i * tile_tokens);
+                int32_t* s = sched + (size_t)(tile_base + i) * 4;
+                s[0] = lane;                     // expert
+                s[1] = off + i * tile_tokens;    // first permuted row
+                s[2] = rows;                     // valid rows in this tile
+                s[3] = i;                        // index of the tile inside its expert
+            }
+            sched_count[4 + lane] = ntile;       // tiles of this expert
         }
-        sched_count[4 + lane] = ntile;       // tiles of this expert
+        if (lane == 63) {
+            // lanes >= E carry zero counts, so lane 63's exclusive sums plus its own are the totals
+            offsets[E] = off + total;
+            sched_count[0] = tile_base + ntile;
+        }
     }
-    if (lane == 63) {
-        // lanes >= E carry zero counts, so lane 63's exclusive sums plus its own are the totals
-        offsets[E] = off + total;
-        sched_count[0] = tile_base + ntile;
+    if (!FUSE_PERMUTE) return;
+    __syncthreads();   // s_off, and this workgroup's own writes to blk_hist, are visible to all its waves from here
+    for (int a = threadIdx.x; a < A; a += 1024) {
+        const int e = topk_idx[a];
+        const int t = a / k;
+        const int blk = t / tokens_per_block;
+        const int pos = s_off[e] + blk_hist[(size_t)blk * 64 + e] + local_rank[a];
+        perm[pos] = a;
+        inv_perm[a] = pos;
+        row_token[pos] = t;
     }
 }
 
@@ -378,10 +399,17 @@ hipError_t launch_routing(const RoutingArgs& a, hipStream_t s) {
         hipLaunchKernelGGL((topk_kernel<8, 1>), dim3(nblk), dim3(64), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
                            a.topk_idx, a.gates, a.local_rank, a.blk_hist);
     if ((err = hipGetLastError()) != hipSuccess) return err;
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, s, a.blk_hist, nblk, a.E, a.tile_tokens, a.counts,
-                       a.offsets, a.sched, a.sched_count);
-    if ((err = hipGetLastError()) != hipSuccess) return err;
     const int A = a.T * a.k;
+    if (a.T <= kSmallRouterMaxT) {   // decode-sized: the scan's workgroup scatters the assignments itself
+        hipLaunchKernelGGL(scan_kernel<true>, dim3(1), dim3(1024), 0, s, a.blk_hist, nblk, a.E, a.tile_tokens, a.counts,
+                           a.offsets, a.sched, a.sched_count, a.topk_idx, a.local_rank, A, a.k, tb, a.perm, a.inv_perm,
+                           a.row_token);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(scan_kernel<false>, dim3(1), dim3(1024), 0, s, a.blk_hist, nblk, a.E, a.tile_tokens, a.counts,
+                       a.offsets, a.sched, a.sched_count, a.topk_idx, a.local_rank, A, a.k, tb, a.perm, a.inv_perm,
+                       a.row_token);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
     hipLaunchKernelGGL(permute_kernel, dim3((A + 255) / 256), dim3(256), 0, s, a.topk_idx, a.local_rank, a.blk_hist,
                        a.offsets, A, a.k, tb, a.perm, a.inv_perm, a.row_token);
     return hipGetLastError();
