@@ -368,6 +368,7 @@ permute_kernel(const int32_t* __restrict__ topk_idx, const int32_t* __restrict__
 // ---------------------------------------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------------------------------------
+constexpr int kTinyRouterMaxT = 128;    // at or below: one token per wave in the partial and top-k kernels
 constexpr int kSmallRouterMaxT = 1024;  // at or below this many tokens the latency-oriented partial kernel runs
 
 int router_tokens_per_block(int T) { return T >= 2048 ? 32 : 8; }
@@ -375,7 +376,11 @@ int router_tokens_per_block(int T) { return T >= 2048 ? 32 : 8; }
 template <bool IS_BF16>
 static hipError_t launch_partials(const RoutingArgs& a, hipStream_t s) {
     const int nseg = a.d / kRouterSegment;
-    if (a.T <= kSmallRouterMaxT) {
+    if (a.T <= kTinyRouterMaxT) {
+        // a handful of tokens: one token per wave, so the chains of different tokens run on different CUs
+        hipLaunchKernelGGL((router_partial_small_kernel<IS_BF16, 1>), dim3(nseg, a.T), dim3(64), 0, s, a.x, a.w_router,
+                           a.T, a.d, a.E, a.partial);
+    } else if (a.T <= kSmallRouterMaxT) {
         constexpr int TW = 4;
         hipLaunchKernelGGL((router_partial_small_kernel<IS_BF16, TW>), dim3(nseg, (a.T + TW - 1) / TW), dim3(64), 0, s,
                            a.x, a.w_router, a.T, a.d, a.E, a.partial);
@@ -394,6 +399,9 @@ hipError_t launch_routing(const RoutingArgs& a, hipStream_t s) {
     const int nblk = (a.T + tb - 1) / tb;
     if (tb == 32)
         hipLaunchKernelGGL((topk_kernel<8, 4>), dim3(nblk), dim3(256), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
+                           a.topk_idx, a.gates, a.local_rank, a.blk_hist);
+    else if (a.T <= kTinyRouterMaxT)
+        hipLaunchKernelGGL((topk_kernel<1, 8>), dim3(nblk), dim3(512), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
                            a.topk_idx, a.gates, a.local_rank, a.blk_hist);
     else
         hipLaunchKernelGGL((topk_kernel<8, 1>), dim3(nblk), dim3(64), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
