@@ -10,6 +10,7 @@ using namespace lexi;
 
 constexpr int kTileTokens = 128;  // token-tile height of the grouped GEMM kernels
 constexpr int kStreamRowsPerExpert = 2;   // mean rows per expert at or below which the routed FFN streams weights
+constexpr int kStreamDownMaxItems = 256;   // (token tiles x column blocks) at or below which the routed down GEMM streams
 constexpr int kStreamDenseRows = 64;      // token count at or below which the shared expert streams weights
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -203,7 +204,9 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     mark(2);
 
     FfnArgs dn{};
-    dn.streaming = stream_routed;
+    // the down projection has few column blocks (d / 256): with few token tiles as well the tile schedule would leave
+    // most CUs idle, so it streams too (16-feature units, K split over the waves)
+    dn.streaming = stream_routed || (int64_t)w.max_tiles * ((ly.d + 255) / 256) <= kStreamDownMaxItems;
     dn.is_bf16 = bf; dn.in = w.act; dn.row_token = nullptr; dn.w0 = ly.w_down; dn.w1 = nullptr; dn.K = ly.F;
     dn.features = ly.d; dn.M = T * k; dn.max_tiles = w.max_tiles; dn.tile_tokens = kTileTokens; dn.sched = w.sched;
     dn.sched_count = w.sched_count; dn.out = w.y_slot;
