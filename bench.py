@@ -24,6 +24,40 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+FFN_SOURCES = ("ffn.hip", "ffn_common.hpp", "ffn_stream.hip", "common.hpp", "kernels.hpp")
+
+
+def ffn_source_digest():
+    """sha256 over the sources of the expert-FFN kernels: stored counter readings are only quoted for this exact code."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in FFN_SOURCES:
+        with open(os.path.join(ROOT, "paper_2509_02753_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def stored_traffic(cfg_name, T):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of this workload
+    (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a copy of known size), or None when
+    there is no summary or the kernel sources have changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"traffic_ffn_gate_up_{cfg_name}_T{T}.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    with open(path) as f:
+        for line in f:
+            if ":" in line and not line.startswith("#"):
+                k, v = line.split(":", 1)
+                kv[k.strip()] = v.strip()
+    if kv.get("ffn_source_sha256") != ffn_source_digest():
+        return None
+    try:
+        return float(kv["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
 def stage_flops_bytes(cfg, T, kvec, counts_per_layer):
     """Algorithmic work of the routed gate/up launch and of the whole stack (only selected experts, only touched weights)."""
     es = 4 if cfg.dtype == "f32" else 2
@@ -50,6 +84,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uniform", action="store_true", help="skip the uniform-k comparison run (profiling: every launch then uses k_vec)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="end with one 256 MiB device-to-device copy kernel (counter runs scale FETCH_SIZE / WRITE_SIZE by it)")
     ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
                     help="replay the stack call from a captured HIP graph (auto: for decode-sized batches, whose steps are launch-bound)")
     args = ap.parse_args()
@@ -153,13 +189,13 @@ def main():
         achieved = gu_flops / L / (gu_ms_avg * 1e-3) / 1e12
         roofline = {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "mfma", "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None, "avg_launch_ms": round(gu_ms_avg, 4),
+                    "traffic": stored_traffic(cfg.name, T), "avg_launch_ms": round(gu_ms_avg, 4),
                     "flops_per_launch": gu_flops / L}
     else:
         achieved = gu_bytes / L / (gu_ms_avg * 1e-3) / 1e9
         roofline = {"kernel": "ffn_mfma_kernel<gate_up>", "bound": "hbm", "achieved": round(achieved, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
-                    "traffic": None, "avg_launch_ms": round(gu_ms_avg, 4),
+                    "traffic": stored_traffic(cfg.name, T), "avg_launch_ms": round(gu_ms_avg, 4),
                     "bytes_per_launch": gu_bytes / L}
     whole = {"flops_per_step": tot_flops, "bytes_per_step": tot_bytes,
              "mfma_frac": round(tot_flops / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
@@ -197,6 +233,13 @@ def main():
         cpu = {"value": round(n / wall, 3), "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
                "sample": f"first {n} tokens of every layer's input through all {L} layers (router + FFN + combine, fp64), {wall:.1f}s"}
         log(f"[bench] cpu oracle: {n} tokens x {L} layers in {wall:.1f}s on {O.num_threads()} threads -> {n / wall:.2f} tokens/s")
+
+    if args.calibration_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)     # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
 
     out = {
         "metric": "MoE-stack tokens/s", "value": round(T / sec, 1), "unit": "tokens/s", "n_gpus": 1,

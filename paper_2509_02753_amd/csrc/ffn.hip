@@ -141,16 +141,18 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
         case 7: k_loop(StageTag<7>{}); break;
         default: k_loop(StageTag<8>{}); break;
     }
-    if (!active) return;
-
     // ---- epilogue: in a 16 x 16 accumulator block a lane owns token (lane % 16) and features 4*(lane/16) + 0..3
+    if (GATEUP) {
+        // The workgroup's 128 tokens x 128 features of silu(gate)*up are transposed through LDS (the token-tile
+        // buffers are free now), so that the global stores are whole 256-byte rows instead of 8-byte pieces.
+        // Row stride 272 B: the 8-byte writes of a half-wave (16 tokens x 2 lane groups) then fall on 64 distinct banks.
+        constexpr int ELD = 136;   // bf16 elements per staged row
+        static_assert(TT * ELD <= 2 * TT * LDS_LD, "the staged output tile must fit the token-tile buffers");
+        bf16_t* stage = &lds_x[0][0];
+        __syncthreads();           // every wave is done reading the token tile
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb) {
-        const int r = tb * 16 + l16;
-        if (r >= ti.rows) continue;
-        const size_t row = (size_t)(ti.row0 + r);
-        if (GATEUP) {
-            bf16_t* o = (bf16_t*)out + row * features + wave_f0 + kq * 4;
+        for (int tb = 0; tb < TB; ++tb) {
+            if (tb * 16 >= ti.rows) break;
 #pragma unroll
             for (int fb = 0; fb < 2; ++fb) {
                 float v[4];
@@ -159,10 +161,28 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
                 u32x2_t pk;
                 pk[0] = pack_bf16x2(v[0], v[1]);
                 pk[1] = pack_bf16x2(v[2], v[3]);
-                *(u32x2_t*)(o + 16 * fb) = pk;
+                *(u32x2_t*)(&stage[(tb * 16 + l16) * ELD + wave * 32 + fb * 16 + kq * 4]) = pk;
             }
-        } else {
-            float* o = (float*)out + row * features + wave_f0 + kq * 4;
+        }
+        __syncthreads();
+        const int c16 = tid & 15;                       // 16-byte chunk of the 256-byte row
+        const int f = cb * 128 + c16 * 8;               // first of its 8 features
+        if (f < features) {                             // (ragged last column block: features is a multiple of 64)
+#pragma unroll
+            for (int p = 0; p < TT / 16; ++p) {
+                const int r = (tid >> 4) + 16 * p;
+                if (r < ti.rows)
+                    *(u32x4_t*)((bf16_t*)out + (size_t)(ti.row0 + r) * features + f) = *(const u32x4_t*)(&stage[r * ELD + c16 * 8]);
+            }
+        }
+    } else {
+        // (a register transpose to 64-byte runs per lane was measured slower than these 16-byte pieces, which L2 merges)
+        if (!active) return;
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            const int r = tb * 16 + l16;
+            if (r >= ti.rows) continue;
+            float* o = (float*)out + (size_t)(ti.row0 + r) * features + wave_f0 + kq * 4;
 #pragma unroll
             for (int fb = 0; fb < WB; ++fb) *(f32x4_t*)(o + 16 * fb) = acc[fb][tb];
         }
