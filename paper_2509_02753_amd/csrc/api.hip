@@ -84,8 +84,8 @@ Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
     w.perm = c.take<int32_t>(A);
     w.inv_perm = c.take<int32_t>(A);
     w.row_token = c.take<int32_t>(A);
-    w.sched = c.take<int32_t>((size_t)w.max_tiles * 4);
-    w.sched_count = c.take<int32_t>(4 + 64);   // [0] tiles in all, [4 + e] tiles of expert e
+    w.sched = c.take<int32_t>((size_t)w.max_tiles * 8);
+    w.sched_count = c.take<int32_t>(4);
     w.act = c.take<char>(A * ly.F * es);
     w.y_slot = c.take<float>(A * ly.d);
     if (ly.F_shared > 0) {

@@ -21,14 +21,21 @@ struct TileInfo {
     int expert, row0, rows;
 };
 
+// Tile schedule written by the scan kernel: one entry of kSchedStride ints per token tile,
+//   (expert, first permuted row of the expert, rows of the expert, index of the tile inside its expert, tiles of the
+//   expert, 0, 0, 0),
+// tiles sorted by expert; sched_count[0] = number of tiles.  Every entry carries its expert's whole extent, so any tile
+// of the expert can be derived from any of its entries with one load.  sched == null: one dense group of M rows.
+constexpr int kSchedStride = 8;
+
 __device__ __forceinline__ bool fetch_tile(const int32_t* sched, const int32_t* sched_count, int tile, int M,
                                            int tile_tokens, TileInfo& ti) {
     if (sched != nullptr) {
         if (tile >= sched_count[0]) return false;
-        const int32_t* s = sched + (size_t)tile * 4;
+        const int32_t* s = sched + (size_t)tile * kSchedStride;
         ti.expert = s[0];
-        ti.row0 = s[1];
-        ti.rows = s[2];
+        ti.row0 = s[1] + s[3] * tile_tokens;
+        ti.rows = min(tile_tokens, s[2] - s[3] * tile_tokens);
         return true;
     }
     ti.expert = 0;
@@ -53,8 +60,6 @@ inline unsigned xcd_grid(int ncb, int max_tiles) {
     return (unsigned)(((total + kXcds - 1) / kXcds) * kXcds);
 }
 
-// sched entry: (expert, first row, rows, index of the tile inside its expert); sched_count[0] = number of tiles,
-// sched_count[4 + e] = number of tiles of expert e.
 __device__ __forceinline__ bool fetch_item(const int32_t* sched, const int32_t* sched_count, int ncb, int M,
                                            int tile_tokens, TileInfo& ti, int& cb) {
     const int ntiles = sched != nullptr ? sched_count[0] : (M + tile_tokens - 1) / tile_tokens;
@@ -64,11 +69,16 @@ __device__ __forceinline__ bool fetch_item(const int32_t* sched, const int32_t* 
     const int item = xcd * per + slot;
     if (slot >= per || item >= total) return false;
     // an expert with n tiles owns n * ncb consecutive items, so tile (item / ncb) belongs to the item's expert
-    int first = 0, n = ntiles;
+    int first = 0, n = ntiles, erow0 = 0, erows = M;
+    ti.expert = 0;
     if (sched != nullptr) {
         const int tq = item / ncb;
-        first = tq - sched[(size_t)tq * 4 + 3];
-        n = sched_count[4 + sched[(size_t)tq * 4]];
+        const int32_t* s = sched + (size_t)tq * kSchedStride;
+        ti.expert = s[0];
+        erow0 = s[1];
+        erows = s[2];
+        first = tq - s[3];
+        n = s[4];
     }
     const int j = item - first * ncb;
     const int gsz = n * kCbGroup;
@@ -76,7 +86,9 @@ __device__ __forceinline__ bool fetch_item(const int32_t* sched, const int32_t* 
     const int gw = min(kCbGroup, ncb - g * kCbGroup);   // the last group of an expert may be narrower
     const int t = r / gw;
     cb = g * kCbGroup + (r - t * gw);
-    return fetch_tile(sched, sched_count, first + t, M, tile_tokens, ti);
+    ti.row0 = erow0 + t * tile_tokens;
+    ti.rows = min(tile_tokens, erows - t * tile_tokens);
+    return true;
 }
 
 hipError_t launch_gateup_stream(const FfnArgs& a, hipStream_t s);

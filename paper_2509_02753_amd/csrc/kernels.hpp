@@ -21,7 +21,7 @@ struct RoutingArgs {
     int32_t* perm;            // [T*k]
     int32_t* inv_perm;        // [T*k]
     int32_t* row_token;       // [T*k]  permuted row -> token
-    int32_t* sched;           // [max_tiles][4]  (expert, first row, rows, 0)
+    int32_t* sched;           // [max_tiles][8]  (expert, its first row, its rows, tile index in it, its tiles, 0, 0, 0)
     int32_t* sched_count;     // [1]
 };
 

@@ -268,7 +268,8 @@ topk_kernel(const float* __restrict__ partial, const float* __restrict__ bias, i
 
 // ---------------------------------------------------------------------------------------------------------
 // scan_kernel (one workgroup of 16 waves): per expert, exclusive prefix of the block histograms (in place),
-// counts, offsets, and the token-tile schedule of the grouped GEMMs: tile i -> (expert, first row, rows).
+// counts, offsets, and the token-tile schedule of the grouped GEMMs: 8 ints per tile (expert, the expert's first
+// row and row count, index of the tile inside the expert, tiles of the expert).
 // Wave w scans its contiguous chunk of blocks, the chunk totals are combined through LDS.
 // ---------------------------------------------------------------------------------------------------------
 // With FUSE_PERMUTE (decode-sized batches) the same workgroup then scatters the assignments (the body of
@@ -318,14 +319,13 @@ scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, in
             counts[lane] = total;
             offsets[lane] = off;
             for (int i = 0; i < ntile; ++i) {
-                const int32_t rows = min(tile_tokens, total - i * tile_tokens);
-                int32_t* s = sched + (size_t)(tile_base + i) * 4;
-                s[0] = lane;                     // expert
-                s[1] = off + i * tile_tokens;    // first permuted row
-                s[2] = rows;                     // valid rows in this tile
-                s[3] = i;                        // index of the tile inside its expert
+                int32_t* s = sched + (size_t)(tile_base + i) * 8;
+                s[0] = lane;      // expert
+                s[1] = off;       // first permuted row of the expert
+                s[2] = total;     // rows of the expert
+                s[3] = i;         // index of the tile inside its expert
+                s[4] = ntile;     // tiles of the expert
             }
-            sched_count[4 + lane] = ntile;       // tiles of this expert
         }
         if (lane == 63) {
             // lanes >= E carry zero counts, so lane 63's exclusive sums plus its own are the totals
