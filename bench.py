@@ -58,6 +58,42 @@ def stored_traffic(cfg_name, T):
         return None
 
 
+def measured_ceilings(torch, P, S, dev):
+    """What this device sustains in plain loops (library probes, timed with events on the launch stream):
+    bf16 MFMA rate on zero operands and on N(0,1) operands (the chip holds a lower clock when the operand bits toggle),
+    and streaming-read bandwidth over a 4 GiB buffer."""
+    def time_ms(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    sink = torch.zeros(256, dtype=torch.float32, device=dev)
+    out = {}
+    for label, sigma in (("zeros", 0.0), ("normal", 1.0)):
+        ops = torch.zeros(64 * 1024, dtype=torch.bfloat16, device=dev)
+        if sigma > 0:
+            S.fill_device(ops, 0x4C455849, 999, sigma)
+        flops = [0.0]
+        def run():
+            flops[0] = P.lexi_probe_mfma_bf16(ops, sink, 4000, 256)
+        ms = time_ms(run, 5)
+        out[f"mfma_bf16_tflops_{label}_operands"] = round(flops[0] / ms / 1e9, 1)
+    buf = torch.empty(1 << 30, dtype=torch.float32, device=dev)     # 4 GiB, far beyond the 256 MB cache
+    buf.fill_(1.0)
+    nbytes = [0.0]
+    def rd():
+        nbytes[0] = P.lexi_probe_hbm_read(buf, sink)
+    ms = time_ms(rd, 5)
+    out["hbm_read_gbs"] = round(nbytes[0] / ms / 1e6, 1)
+    del buf
+    return out
+
+
 def stage_flops_bytes(cfg, T, kvec, counts_per_layer):
     """Algorithmic work of the routed gate/up launch and of the whole stack (only selected experts, only touched weights)."""
     es = 4 if cfg.dtype == "f32" else 2
@@ -84,6 +120,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uniform", action="store_true", help="skip the uniform-k comparison run (profiling: every launch then uses k_vec)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the matrix-core / HBM ceiling probes")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="end with one 256 MiB device-to-device copy kernel (counter runs scale FETCH_SIZE / WRITE_SIZE by it)")
     ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
@@ -205,9 +242,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle as O
-        # about 15 s of oracle work on 16 cores: the oracle does ~1 GFLOP/s per core on the FFN loops
-        per_token = sum(int(k) * 6.0 * cfg.d * cfg.F + 6.0 * cfg.d * cfg.F_shared + 2.0 * cfg.d * cfg.E for k in kvec)
-        n = args.cpu_sample_tokens or max(1, min(T, int(15.0 * 16e9 / per_token)))
+        # sized for about 15 s of oracle work: a 32-token pilot on layer 0 measures this host's rate first
+        n = args.cpu_sample_tokens
 
         def to_host_layer(tensors):
             """Device tensors of one layer -> numpy (bf16 as uint16 bit patterns); the inputs, copied D2H."""
@@ -221,6 +257,16 @@ def main():
                     h[name] = t.cpu().numpy()
             return h
 
+        if n is None:
+            hl0 = O.Layer.from_tensors(cfg, to_host_layer(S.device_layer(cfg, 0, dev)))
+            npilot = min(T, 32)
+            xp = x[0, :npilot].contiguous()
+            xp = xp.view(torch.int16).cpu().numpy().view(np.uint16) if tdt == torch.bfloat16 else xp.cpu().numpy()
+            t1 = time.perf_counter()
+            O.moe_layer(hl0, xp, int(kvec[0]), round_act=True)
+            rate = npilot / max(time.perf_counter() - t1, 1e-6)          # tokens/s of one layer
+            del hl0
+            n = max(1, min(T, int(15.0 * rate / L)))
         wall = 0.0
         for l in range(L):
             hl = O.Layer.from_tensors(cfg, to_host_layer(S.device_layer(cfg, l, dev)))  # same seeded tensors, row-major
@@ -233,6 +279,10 @@ def main():
         cpu = {"value": round(n / wall, 3), "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
                "sample": f"first {n} tokens of every layer's input through all {L} layers (router + FFN + combine, fp64), {wall:.1f}s"}
         log(f"[bench] cpu oracle: {n} tokens x {L} layers in {wall:.1f}s on {O.num_threads()} threads -> {n / wall:.2f} tokens/s")
+
+    ceilings = None if args.no_ceilings else measured_ceilings(torch, P, S, dev)
+    if ceilings:
+        log("[bench] measured ceilings: " + ", ".join(f"{k}={v}" for k, v in ceilings.items()))
 
     if args.calibration_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
@@ -251,7 +301,7 @@ def main():
         "uniform_k_tokens_per_s": round(T / sec_uniform, 1) if sec_uniform else None,
         "speedup_vs_uniform_k": round(sec_uniform / sec, 4) if sec_uniform else None,
         "stage_ms_per_step": {n: round(float(v), 4) for n, v in zip(P.STAGE_NAMES, per_stage)},
-        "roofline": roofline, "whole_path": whole, "cpu_baseline": cpu,
+        "roofline": roofline, "whole_path": whole, "measured_ceilings": ceilings, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 

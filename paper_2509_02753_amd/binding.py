@@ -19,7 +19,8 @@ LEXI_F32, LEXI_BF16 = 0, 1
 SHARED_NONE, SHARED_UNGATED, SHARED_SIGMOID = 0, 1, 2
 
 EXPORTS = ("lexi_pack_weights", "lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward",
-           "lexi_moe_stack_forward_profiled", "lexi_strerror", "lexi_moe_version")
+           "lexi_moe_stack_forward_profiled", "lexi_probe_mfma_bf16", "lexi_probe_hbm_read", "lexi_strerror",
+           "lexi_moe_version")
 N_STAGE_EVENTS = 6
 STAGE_NAMES = ("routing", "gate_up", "down", "shared", "combine")
 
@@ -66,6 +67,10 @@ def _load() -> ctypes.CDLL:
                                            i32, i32, i32, vp, sz, vp, ctypes.POINTER(lexi_routing_out_t)]
     lib.lexi_moe_stack_forward_profiled.restype = i32
     lib.lexi_moe_stack_forward_profiled.argtypes = lib.lexi_moe_stack_forward.argtypes + [ctypes.POINTER(lexi_stage_events_t)]
+    lib.lexi_probe_mfma_bf16.restype = i32
+    lib.lexi_probe_mfma_bf16.argtypes = [vp, vp, i32, i32, vp]
+    lib.lexi_probe_hbm_read.restype = i32
+    lib.lexi_probe_hbm_read.argtypes = [vp, sz, vp, vp]
     lib.lexi_strerror.restype = ctypes.c_char_p
     lib.lexi_strerror.argtypes = [i32]
     lib.lexi_moe_version.restype = ctypes.c_char_p
@@ -218,6 +223,24 @@ def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: tor
                                          _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg)
     if st != LEXI_OK:
         raise LexiError(st, "lexi_moe_stack_forward")
+
+
+def lexi_probe_mfma_bf16(operands: torch.Tensor, sink: torch.Tensor, iters: int, workgroups: int,
+                         stream: Optional[torch.cuda.Stream] = None) -> float:
+    """Enqueue the matrix-core probe; returns the flops it executes (time it with events)."""
+    st = _lib.lexi_probe_mfma_bf16(_dp(operands), _dp(sink), int(iters), int(workgroups), _stream_ptr(stream))
+    if st != LEXI_OK:
+        raise LexiError(st, "lexi_probe_mfma_bf16")
+    return float(workgroups) * 4 * iters * 16 * 32768
+
+
+def lexi_probe_hbm_read(src: torch.Tensor, sink: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> float:
+    """Enqueue one streaming read of `src`; returns the bytes read (time it with events)."""
+    nbytes = src.numel() * src.element_size()
+    st = _lib.lexi_probe_hbm_read(_dp(src), nbytes, _dp(sink), _stream_ptr(stream))
+    if st != LEXI_OK:
+        raise LexiError(st, "lexi_probe_hbm_read")
+    return float(nbytes)
 
 
 class StageEvents:
