@@ -211,3 +211,16 @@ def moe_stack(layers, xs, k_vec, tokens=None, round_act: bool = False, routing_o
         x = xs[l] if isinstance(xs, (list, tuple)) else xs
         res.append(moe_layer(ly, x, int(k_vec[l]), tokens=tokens, round_act=round_act, routing_only=routing_only))
     return res
+
+
+def profile_layer(layer: Layer, x, k_base: int, k_list, round_act: bool = False) -> np.ndarray:
+    """One iteration of the Stage-1 top-k perturbation profiling (paper Algorithm 1) on one input X:
+    Y_base = f_moe(X; k_base), then for every k of the list Delta_k = || f_moe(X; k) - Y_base ||_F  (fp64).
+    Taken in the algorithm's own order: the baseline pass first, then one full pass per target k; the average over
+    iterations that the algorithm ends with is left to the caller."""
+    y_base = moe_layer(layer, x, int(k_base), round_act=round_act).out
+    deltas = np.empty(len(k_list), dtype=np.float64)
+    for i, k in enumerate(k_list):
+        y_k = moe_layer(layer, x, int(k), round_act=round_act).out
+        deltas[i] = np.sqrt(np.sum((y_k - y_base) ** 2))
+    return deltas

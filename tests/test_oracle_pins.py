@@ -380,3 +380,48 @@ def test_bad_k_is_rejected():
     for k in (0, 5, -1):
         with pytest.raises(RuntimeError):
             O.moe_layer(ly, x, k)
+
+
+# ---------------------------------------------------------------- Stage-1 perturbation profiling (Algorithm 1)
+def _tiny_layer(rng, d=128, E=6, F=64, identical=False):
+    wg = rng.normal(0, 0.3, (E, F, d)).astype(np.float32)
+    wu = rng.normal(0, 0.3, (E, F, d)).astype(np.float32)
+    wd = rng.normal(0, 0.3, (E, d, F)).astype(np.float32)
+    if identical:
+        wg[:], wu[:], wd[:] = wg[0], wu[0], wd[0]
+    return O.Layer(d, E, F, "f32", rng.normal(0, 0.5, (d, E)).astype(np.float32), wg, wu, wd)
+
+
+def test_profile_delta_is_zero_at_k_base_and_for_identical_experts():
+    """Delta_{k_base} = 0 exactly; with identical experts every k gives E_0(x) (gates sum to 1), so every Delta is 0 up
+    to the fp32 storage of the gates (2^-24 relative per gate)."""
+    rng = np.random.default_rng(21)
+    x = rng.normal(0, 1, (9, 128)).astype(np.float32)
+    ly = _tiny_layer(rng)
+    d = O.profile_layer(ly, x, 4, [1, 2, 3, 4])
+    assert d[3] == 0.0 and np.all(d[:3] > 0)
+    same = _tiny_layer(rng, identical=True)
+    ref = np.sqrt(np.sum(O.moe_layer(same, x, 4).out ** 2))
+    assert np.all(O.profile_layer(same, x, 4, [1, 2, 3]) <= 1e-6 * ref)
+
+
+def test_profile_delta_matches_the_closed_form_in_the_dropped_experts():
+    """Y_k - Y_base = sum_s (g_k[s]*[s<k] - g_base[s]) * E_{sel_s}(x): recomputed here from the gates' closed form
+    (softmax over prefixes of the selected logits) and per-expert outputs, without calling the profiling function."""
+    rng = np.random.default_rng(22)
+    T, kb = 7, 5
+    x = rng.normal(0, 1, (T, 128)).astype(np.float32)
+    ly = _tiny_layer(rng, E=6)
+    base = O.moe_layer(ly, x, kb)
+    got = O.profile_layer(ly, x, kb, [1, 3])
+    for i, k in enumerate((1, 3)):
+        total = 0.0
+        for t in range(T):
+            sel = base.topk_idx[t]
+            l = base.logits[t][sel].astype(np.float64)
+            gb = np.exp(l - l[0]) / np.exp(l - l[0]).sum()
+            gk = np.zeros(kb)
+            gk[:k] = np.exp(l[:k] - l[0]) / np.exp(l[:k] - l[0]).sum()
+            diff = sum((gk[s] - gb[s]) * O.expert_ffn(ly, int(sel[s]), x, t) for s in range(kb))
+            total += float(np.sum(diff ** 2))
+        assert abs(got[i] - np.sqrt(total)) <= 1e-6 * np.sqrt(total)   # the oracle stores its gates in fp32
