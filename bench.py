@@ -120,6 +120,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uniform", action="store_true", help="skip the uniform-k comparison run (profiling: every launch then uses k_vec)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
+    ap.add_argument("--no-stage1", action="store_true", help="skip the Stage-1 profiling timing")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the matrix-core / HBM ceiling probes")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="end with one 256 MiB device-to-device copy kernel (counter runs scale FETCH_SIZE / WRITE_SIZE by it)")
@@ -280,6 +281,39 @@ def main():
                "sample": f"first {n} tokens of every layer's input through all {L} layers (router + FFN + combine, fp64), {wall:.1f}s"}
         log(f"[bench] cpu oracle: {n} tokens x {L} layers in {wall:.1f}s on {O.num_threads()} threads -> {n / wall:.2f} tokens/s")
 
+    # ---- Stage-1 profiling (Algorithm 1), one iteration on layer 0: all k of the search space from one baseline pass,
+    #      against the algorithm as printed (1 + |list| full forward passes)
+    stage1 = None
+    if not args.no_stage1:
+        kb = int(cfg.k_base)
+        klist = list(range(1, kb + 1))
+        yl = torch.empty((T, cfg.d), dtype=torch.float32, device=dev)
+
+        def fused():
+            return P.lexi_moe_profile_layer(layers[0], x[0], kb, klist, workspace=ws_prof)
+
+        def printed():
+            for kk in [kb] + klist:
+                P.lexi_moe_layer_forward(layers[0], x[0], yl, kk, ws)
+
+        need = P.binding._lib.lexi_moe_profile_workspace_bytes(layers[0].c, T, kb, len(klist))
+        ws_prof = torch.empty(int(need), dtype=torch.uint8, device=dev)
+        times = []
+        for fn in (fused, printed):
+            fn()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t1) / args.steps * 1e3)
+        stage1 = {"layer": 0, "k_base": kb, "k_list": klist, "ms_per_iteration": round(times[0], 4),
+                  "ms_as_printed": round(times[1], 4), "speedup": round(times[1] / times[0], 3),
+                  "tokens_per_s": round(T / times[0] * 1e3, 1)}
+        log(f"[bench] stage-1 profiling, layer 0, k in 1..{kb}: {times[0]:.3f} ms per iteration "
+            f"(vs {times[1]:.3f} ms as {1 + len(klist)} forward passes)")
+        del ws_prof, yl
+
     ceilings = None if args.no_ceilings else measured_ceilings(torch, P, S, dev)
     if ceilings:
         log("[bench] measured ceilings: " + ", ".join(f"{k}={v}" for k, v in ceilings.items()))
@@ -301,7 +335,8 @@ def main():
         "uniform_k_tokens_per_s": round(T / sec_uniform, 1) if sec_uniform else None,
         "speedup_vs_uniform_k": round(sec_uniform / sec, 4) if sec_uniform else None,
         "stage_ms_per_step": {n: round(float(v), 4) for n, v in zip(P.STAGE_NAMES, per_stage)},
-        "roofline": roofline, "whole_path": whole, "measured_ceilings": ceilings, "cpu_baseline": cpu,
+        "roofline": roofline, "whole_path": whole, "measured_ceilings": ceilings, "stage1_profiling": stage1,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 

@@ -150,6 +150,19 @@ lexi_status lexi_moe_stack_forward_profiled(const lexi_layer_t* layers, int32_t 
                                             const lexi_routing_out_t* dbg_per_layer,
                                             const lexi_stage_events_t* events_per_layer);
 
+/* One iteration of the Stage-1 top-k perturbation profiling (Algorithm 1) on one input X:
+ *     delta[i] = || f_moe(X; k_list[i]) - f_moe(X; k_base) ||_F ,   1 <= k_list[i] <= k_base <= E,  n_k <= 64.
+ *   The selection order is total, so TopK_k is a prefix of TopK_{k_base}: one routing pass and one pass of the expert
+ *   GEMMs at k_base serve every k of the list (the algorithm as printed runs 1 + n_k full passes), and a shared
+ *   expert, which adds the same vector to both outputs, drops out of the difference.
+ *   x [T][d] of layer->dtype (T >= 1); k_list: HOST int32[n_k]; delta: DEVICE float[n_k], receives this X's
+ *   deviations (averaging over iterations, the algorithm's last step, is the caller's).  workspace: device scratch of
+ *   at least lexi_moe_profile_workspace_bytes(layer, T, k_base, n_k) bytes.  Asynchronous on hip_stream. */
+size_t lexi_moe_profile_workspace_bytes(const lexi_layer_t* layer, int32_t T_max, int32_t k_base, int32_t n_k);
+lexi_status lexi_moe_profile_layer(const lexi_layer_t* layer, const void* x, int32_t T, int32_t k_base,
+                                   const int32_t* k_list, int32_t n_k, float* delta, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+
 /* Device ceilings for the roofline report (not part of the MoE path; the caller times the launches with events).
  *   lexi_probe_mfma_bf16: `workgroups` workgroups of 4 waves, each wave issuing iters * 16 independent
  *     v_mfma_f32_32x32x16_bf16 (32768 flops each) on operand fragments read once from `operands` (device, at least

@@ -19,7 +19,8 @@ LEXI_F32, LEXI_BF16 = 0, 1
 SHARED_NONE, SHARED_UNGATED, SHARED_SIGMOID = 0, 1, 2
 
 EXPORTS = ("lexi_pack_weights", "lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward",
-           "lexi_moe_stack_forward_profiled", "lexi_probe_mfma_bf16", "lexi_probe_hbm_read", "lexi_strerror",
+           "lexi_moe_stack_forward_profiled", "lexi_moe_profile_workspace_bytes", "lexi_moe_profile_layer",
+           "lexi_probe_mfma_bf16", "lexi_probe_hbm_read", "lexi_strerror",
            "lexi_moe_version")
 N_STAGE_EVENTS = 6
 STAGE_NAMES = ("routing", "gate_up", "down", "shared", "combine")
@@ -67,6 +68,10 @@ def _load() -> ctypes.CDLL:
                                            i32, i32, i32, vp, sz, vp, ctypes.POINTER(lexi_routing_out_t)]
     lib.lexi_moe_stack_forward_profiled.restype = i32
     lib.lexi_moe_stack_forward_profiled.argtypes = lib.lexi_moe_stack_forward.argtypes + [ctypes.POINTER(lexi_stage_events_t)]
+    lib.lexi_moe_profile_workspace_bytes.restype = sz
+    lib.lexi_moe_profile_workspace_bytes.argtypes = [ctypes.POINTER(lexi_layer_t), i32, i32, i32]
+    lib.lexi_moe_profile_layer.restype = i32
+    lib.lexi_moe_profile_layer.argtypes = [ctypes.POINTER(lexi_layer_t), vp, i32, i32, ctypes.POINTER(i32), i32, vp, vp, sz, vp]
     lib.lexi_probe_mfma_bf16.restype = i32
     lib.lexi_probe_mfma_bf16.argtypes = [vp, vp, i32, i32, vp]
     lib.lexi_probe_hbm_read.restype = i32
@@ -223,6 +228,25 @@ def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: tor
                                          _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg)
     if st != LEXI_OK:
         raise LexiError(st, "lexi_moe_stack_forward")
+
+
+def lexi_moe_profile_layer(layer: Layer, x: torch.Tensor, k_base: int, k_list: Sequence[int],
+                           workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Delta_k = ||f_moe(x; k) - f_moe(x; k_base)||_F for every k of k_list (Algorithm 1, one iteration), as a device
+    float tensor [len(k_list)].  The workspace is allocated here when none is given."""
+    T, n = int(x.shape[0]), len(k_list)
+    need = int(_lib.lexi_moe_profile_workspace_bytes(ctypes.byref(layer.c), T, int(k_base), n))
+    if need == 0:
+        raise LexiError(-2, "lexi_moe_profile_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    delta = torch.empty(n, dtype=torch.float32, device=x.device)
+    kl = (ctypes.c_int32 * n)(*[int(k) for k in k_list])
+    st = _lib.lexi_moe_profile_layer(ctypes.byref(layer.c), _dp(x), T, int(k_base), kl, n, _dp(delta), _dp(workspace),
+                                     workspace.numel(), _stream_ptr(stream))
+    if st != LEXI_OK:
+        raise LexiError(st, "lexi_moe_profile_layer")
+    return delta
 
 
 def lexi_probe_mfma_bf16(operands: torch.Tensor, sink: torch.Tensor, iters: int, workgroups: int,

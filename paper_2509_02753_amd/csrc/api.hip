@@ -137,6 +137,44 @@ lexi_status check_call(const lexi_layer_t* ly, const void* x, const void* y, int
     return LEXI_OK;
 }
 
+// Routing and the routed expert GEMMs of one layer at top-k = k: fills the routing arrays, act and y_slot of `w`.
+lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t k, Workspace& w, hipStream_t s,
+                       const lexi_stage_events_t* events) {
+    auto mark = [&](int i) {
+        if (events && events->ev[i]) (void)hipEventRecord((hipEvent_t)events->ev[i], s);
+    };
+    const bool bf = ly.dtype == LEXI_BF16;
+    RoutingArgs r{};
+    r.x = x; r.is_bf16 = bf; r.w_router = ly.w_router; r.bias = ly.router_bias;
+    r.T = T; r.d = ly.d; r.E = ly.E; r.k = k; r.tile_tokens = kTileTokens;
+    r.partial = w.partial; r.topk_idx = w.topk_idx; r.gates = w.gates; r.local_rank = w.local_rank; r.blk_hist = w.blk_hist;
+    r.counts = w.counts; r.offsets = w.offsets; r.perm = w.perm; r.inv_perm = w.inv_perm; r.row_token = w.row_token;
+    r.sched = w.sched; r.sched_count = w.sched_count;
+    if (launch_routing(r, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+    mark(1);
+
+    // few rows per expert (decode): the weight-streaming schedule; otherwise the MFMA tile schedule
+    const bool stream_routed = (int64_t)T * k <= (int64_t)kStreamRowsPerExpert * ly.E;
+    FfnArgs g{};
+    g.streaming = stream_routed;
+    g.is_bf16 = bf; g.in = x; g.row_token = w.row_token; g.w0 = ly.w_gate; g.w1 = ly.w_up; g.K = ly.d;
+    g.features = ly.F; g.M = T * k; g.max_tiles = w.max_tiles; g.tile_tokens = kTileTokens; g.sched = w.sched;
+    g.sched_count = w.sched_count; g.out = w.act;
+    if (launch_gateup(g, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+    mark(2);
+
+    FfnArgs dn{};
+    // the down projection has few column blocks (d / 256): with few token tiles as well the tile schedule would leave
+    // most CUs idle, so it streams too (16-feature units, K split over the waves)
+    dn.streaming = stream_routed || (int64_t)w.max_tiles * ((ly.d + 255) / 256) <= kStreamDownMaxItems;
+    dn.is_bf16 = bf; dn.in = w.act; dn.row_token = nullptr; dn.w0 = ly.w_down; dn.w1 = nullptr; dn.K = ly.F;
+    dn.features = ly.d; dn.M = T * k; dn.max_tiles = w.max_tiles; dn.tile_tokens = kTileTokens; dn.sched = w.sched;
+    dn.sched_count = w.sched_count; dn.out = w.y_slot;
+    if (launch_down(dn, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+    mark(3);
+    return LEXI_OK;
+}
+
 // One layer, arguments already validated.
 lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_dtype, int32_t T, int32_t k,
                       void* workspace, hipStream_t s, const lexi_routing_out_t* dbg,
@@ -184,34 +222,10 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
         if (hipEventRecord(side->join, side->stream) != hipSuccess) return LEXI_ERR_LAUNCH;
     }
 
-    RoutingArgs r{};
-    r.x = x; r.is_bf16 = bf; r.w_router = ly.w_router; r.bias = ly.router_bias;
-    r.T = T; r.d = ly.d; r.E = ly.E; r.k = k; r.tile_tokens = kTileTokens;
-    r.partial = w.partial; r.topk_idx = w.topk_idx; r.gates = w.gates; r.local_rank = w.local_rank; r.blk_hist = w.blk_hist;
-    r.counts = w.counts; r.offsets = w.offsets; r.perm = w.perm; r.inv_perm = w.inv_perm; r.row_token = w.row_token;
-    r.sched = w.sched; r.sched_count = w.sched_count;
-    if (launch_routing(r, s) != hipSuccess) return LEXI_ERR_LAUNCH;
-    mark(1);
-
-    // few rows per expert (decode): the weight-streaming schedule; otherwise the MFMA tile schedule
-    const bool stream_routed = (int64_t)T * k <= (int64_t)kStreamRowsPerExpert * ly.E;
-    FfnArgs g{};
-    g.streaming = stream_routed;
-    g.is_bf16 = bf; g.in = x; g.row_token = w.row_token; g.w0 = ly.w_gate; g.w1 = ly.w_up; g.K = ly.d;
-    g.features = ly.F; g.M = T * k; g.max_tiles = w.max_tiles; g.tile_tokens = kTileTokens; g.sched = w.sched;
-    g.sched_count = w.sched_count; g.out = w.act;
-    if (launch_gateup(g, s) != hipSuccess) return LEXI_ERR_LAUNCH;
-    mark(2);
-
-    FfnArgs dn{};
-    // the down projection has few column blocks (d / 256): with few token tiles as well the tile schedule would leave
-    // most CUs idle, so it streams too (16-feature units, K split over the waves)
-    dn.streaming = stream_routed || (int64_t)w.max_tiles * ((ly.d + 255) / 256) <= kStreamDownMaxItems;
-    dn.is_bf16 = bf; dn.in = w.act; dn.row_token = nullptr; dn.w0 = ly.w_down; dn.w1 = nullptr; dn.K = ly.F;
-    dn.features = ly.d; dn.M = T * k; dn.max_tiles = w.max_tiles; dn.tile_tokens = kTileTokens; dn.sched = w.sched;
-    dn.sched_count = w.sched_count; dn.out = w.y_slot;
-    if (launch_down(dn, s) != hipSuccess) return LEXI_ERR_LAUNCH;
-    mark(3);
+    {
+        const lexi_status st = run_routed(ly, x, T, k, w, s, events);
+        if (st != LEXI_OK) return st;
+    }
 
     if (ly.F_shared > 0) {
         if (side) {
@@ -312,6 +326,43 @@ lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const 
                                    void* hip_stream, const lexi_routing_out_t* dbg_per_layer) {
     return lexi_moe_stack_forward_profiled(layers, L, k_vec, x, x_layer_stride, y, y_layer_stride, y_dtype, T, mode,
                                            workspace, workspace_bytes, hip_stream, dbg_per_layer, nullptr);
+}
+
+size_t lexi_moe_profile_workspace_bytes(const lexi_layer_t* layer, int32_t T_max, int32_t k_base, int32_t n_k) {
+    if (!layer || check_layer(layer) != LEXI_OK || T_max < 0 || k_base < 1 || k_base > layer->E || n_k < 1 ||
+        n_k > kProfileMaxK)
+        return 0;
+    return carve(*layer, T_max, k_base, nullptr).bytes + align_up((size_t)n_k * T_max * sizeof(float), 256);
+}
+
+lexi_status lexi_moe_profile_layer(const lexi_layer_t* layer, const void* x, int32_t T, int32_t k_base,
+                                   const int32_t* k_list, int32_t n_k, float* delta, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+    lexi_status st = check_layer(layer);
+    if (st != LEXI_OK) return st;
+    if (!k_list || !delta) return LEXI_ERR_NULL;
+    if (T < 1 || n_k < 1 || n_k > kProfileMaxK) return LEXI_ERR_SHAPE;
+    if (k_base < 1 || k_base > layer->E) return LEXI_ERR_BAD_K;
+    if ((int64_t)T * k_base >= (1 << 24)) return LEXI_ERR_SHAPE;
+    ProfileKList kl{};
+    kl.n = n_k;
+    for (int i = 0; i < n_k; ++i) {
+        if (k_list[i] < 1 || k_list[i] > k_base) return LEXI_ERR_BAD_K;
+        kl.k[i] = k_list[i];
+    }
+    if (!x || !workspace) return LEXI_ERR_NULL;
+    if (misaligned(x) || misaligned(workspace) || misaligned(delta)) return LEXI_ERR_ALIGN;
+    Workspace w = carve(*layer, T, k_base, workspace);
+    if (workspace_bytes < w.bytes + align_up((size_t)n_k * T * sizeof(float), 256)) return LEXI_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    st = run_routed(*layer, x, T, k_base, w, s, nullptr);
+    if (st != LEXI_OK) return st;
+    ProfileArgs p{};
+    p.y_slot = w.y_slot; p.inv_perm = w.inv_perm; p.gates = w.gates;
+    p.T = T; p.d = layer->d; p.k_base = k_base; p.klist = kl;
+    p.part = (float*)((char*)workspace + w.bytes);
+    p.delta = delta;
+    return launch_profile(p, s) == hipSuccess ? LEXI_OK : LEXI_ERR_LAUNCH;
 }
 
 const char* lexi_strerror(int32_t status) {

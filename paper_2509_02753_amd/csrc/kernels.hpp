@@ -70,4 +70,21 @@ struct CombineArgs {
 };
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
 
+// Stage-1 profiling: squared-difference reduction over the slot rows of one baseline pass.
+constexpr int kProfileMaxK = 64;
+struct ProfileKList {          // passed to the kernel by value
+    int32_t n;
+    int32_t k[kProfileMaxK];
+};
+struct ProfileArgs {
+    const float* y_slot;       // [T*k_base][d] fp32, permuted rows
+    const int32_t* inv_perm;   // [T*k_base]
+    const float* gates;        // [T*k_base] baseline gates
+    int T, d, k_base;
+    ProfileKList klist;
+    float* part;               // [n][T] per-token squared norms
+    float* delta;              // [n]
+};
+hipError_t launch_profile(const ProfileArgs& a, hipStream_t s);
+
 }  // namespace lexi
