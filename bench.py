@@ -108,6 +108,58 @@ def stage_flops_bytes(cfg, T, kvec, counts_per_layer):
     return gateup_flops, gateup_bytes, total_flops, total_bytes
 
 
+def pruning_sweep(args, cfg0, T):
+    """Fig. 2 analogue on synthetic weights: tokens/s of the whole stack against the number of active experts k
+    (uniform over the layers) for the baseline shape and for the SHAPES of inter- (fewer experts) and intra-expert
+    (narrower FFN) pruning at 12.5 / 25 / 50 %, plus the per-layer k vector on the baseline shape.  One JSON line."""
+    import numpy as np
+    import torch
+
+    import lexi_synth as S
+    import paper_2509_02753_amd as P
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    variants = [("base", 0.0, 0.0)] + [("inter", p, 0.0) for p in (0.125, 0.25, 0.5)] + [("intra", 0.0, p) for p in (0.125, 0.25, 0.5)]
+    rows = []
+    for kind, pi, pa in variants:
+        cfg = S.pruned(cfg0, inter=pi, intra=pa) if (pi or pa) else cfg0
+        L = args.layers if args.layers else cfg.L
+        layers = []
+        for l in range(L):
+            rm = S.device_layer(cfg, l, dev)
+            layers.append(P.Layer.from_tensors(rm, shared_kind=cfg.shared_kind))
+            del rm
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+        x = torch.empty((L, T, cfg.d), dtype=tdt, device=dev)
+        for l in range(L):
+            S.fill_device(x[l], cfg.seed, S.tensor_id(l, S.KIND_X), cfg.sigma_x)
+        y = torch.empty((L, T, cfg.d), dtype=torch.float32, device=dev)
+        ws = P.alloc_workspace(layers, T, int(cfg.k_base))
+        arr = P.binding._layer_array(layers)
+        kvecs = [(f"uniform k={k}", np.full(L, k, dtype=np.int32)) for k in range(1, cfg.k_base + 1)]
+        if kind == "base":
+            kvecs.append(("per-layer k vector", cfg.k_lexi()[:L]))
+        for label, kv in kvecs:
+            for _ in range(args.warmup):
+                P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr)
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / args.steps
+            rows.append({"variant": kind if kind == "base" else f"{kind} {100 * (pi or pa):g}%", "E": cfg.E, "F": cfg.F,
+                         "k": label, "active_experts_sum": int(kv.sum()), "ms_per_step": round(sec * 1e3, 4),
+                         "tokens_per_s": round(T / sec, 1),
+                         "weight_gb": round(cfg.weight_bytes() * L / cfg.L / 1e9, 2)})
+            log(f"[sweep] {rows[-1]}")
+        del layers, x, y, ws, arr
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "MoE-stack tokens/s", "sweep": "pruning shapes vs active experts", "unit": "tokens/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                      "config": {"workload": f"{cfg0.name} L={args.layers or cfg0.L} d={cfg0.d} T={T}"}, "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,6 +176,8 @@ def main():
     ap.add_argument("--no-ceilings", action="store_true", help="skip the matrix-core / HBM ceiling probes")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="end with one 256 MiB device-to-device copy kernel (counter runs scale FETCH_SIZE / WRITE_SIZE by it)")
+    ap.add_argument("--sweep", default=None, choices=["pruning"],
+                    help="instead of the benchmark line: tokens/s vs active experts for the baseline and the pruned shapes")
     ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
                     help="replay the stack call from a captured HIP graph (auto: for decode-sized batches, whose steps are launch-bound)")
     args = ap.parse_args()
@@ -139,6 +193,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = S.CONFIGS[args.config]
     T = args.T if args.T is not None else cfg.T_regimes[0]
+    if args.sweep == "pruning":
+        return pruning_sweep(args, cfg, T)
     L = args.layers if args.layers else cfg.L
     kvec = (cfg.k_lexi() if args.kvec == "lexi" else cfg.k_uniform())[:L]
     kuni = cfg.k_uniform()[:L]

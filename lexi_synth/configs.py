@@ -84,3 +84,17 @@ def mini(cfg: MoEConfig, L: int = 2, d: int = 256, F: int = 384, F_shared: Optio
         fixed = tuple([cfg.k_min] * (L // 2) + [cfg.k_max] * (L - L // 2))
         budget = sum(fixed)
     return replace(cfg, name=cfg.name + "_mini", L=L, d=d, F=F, F_shared=fs, budget=budget, fixed_kvec=fixed)
+
+
+def pruned(cfg: MoEConfig, inter: float = 0.0, intra: float = 0.0) -> MoEConfig:
+    """The SHAPE of an expert-pruned model (the paper's comparison methods, Sec. 3 "Inter and Intra Expert Pruning"):
+    inter-pruning removes a fraction of the experts (and their router columns) and keeps k; intra-pruning shrinks
+    every expert's FFN width.  Which experts or channels go is decided from calibration data in those methods and
+    is not modelled: the weights stay synthetic, only the shapes change.  E' = floor(E (1 - inter));
+    F' = F (1 - intra) rounded down to a multiple of 64 (the kernels' granularity)."""
+    E = max(1, int(cfg.E * (1.0 - inter)))
+    F = max(64, int(cfg.F * (1.0 - intra)) // 64 * 64)
+    k_base = min(cfg.k_base, E)
+    tag = (f"_inter{int(round(inter * 1000))}" if inter else "") + (f"_intra{int(round(intra * 1000))}" if intra else "")
+    return replace(cfg, name=cfg.name + tag, E=E, F=F, k_base=k_base, k_max=min(cfg.k_max, E), k_min=min(cfg.k_min, E),
+                   budget=min(cfg.budget, cfg.L * min(cfg.k_max, E)))

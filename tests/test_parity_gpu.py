@@ -28,6 +28,19 @@ def test_mini_layers_all_tokens(name, T, k):
     run_and_check_layer(cfg, 0, T, k)
 
 
+@pytest.mark.parametrize("name,inter,intra,T,k", [
+    ("c2_olmoe", 0.125, 0.0, 260, 8), ("c2_olmoe", 0.5, 0.0, 131, 3), ("c3_qwen15", 0.25, 0.0, 200, 4),
+    ("c2_olmoe", 0.0, 0.125, 260, 8), ("c3_qwen15", 0.0, 0.5, 150, 2), ("c5_dsv2lite", 0.25, 0.25, 64, 6),
+])
+def test_pruned_shapes(name, inter, intra, T, k):
+    """Shapes of the paper's comparison methods (Sec. 3): fewer experts (E not a power of two: 56, 45, 32, 48) and
+    narrower expert FFNs (widths that are odd multiples of 64), every token compared."""
+    base = S.mini(S.CONFIGS[name], L=1, d=256, F=512)
+    cfg = S.pruned(base, inter=inter, intra=intra)
+    assert (cfg.E, cfg.F) != (base.E, base.F)
+    run_and_check_layer(cfg, 0, T, k)
+
+
 def test_repeated_calls_and_k_changes_leave_no_state():
     """UpdateTopk changes k only: k=2, then k=8, then k=2 again reproduces the first result bit for bit."""
     import torch
