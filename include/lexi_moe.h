@@ -163,6 +163,18 @@ lexi_status lexi_moe_profile_layer(const lexi_layer_t* layer, const void* x, int
                                    const int32_t* k_list, int32_t n_k, float* delta, void* workspace,
                                    size_t workspace_bytes, void* hip_stream);
 
+/* LExI Stage 2 (Algorithm 2): evolutionary search for the per-layer allocation k* = (k_1 .. k_L) that minimises
+ * phi(k) = sum_j D[j][k_j] subject to sum_j k_j = B and k_min <= k_j <= k_max.  HOST function, HOST pointers, no GPU.
+ *   D: [L][k_max + 1] doubles, entry [j][k] = Stage-1 loss of layer j at top-k = k (entries below k_min are not read);
+ *   n_pop >= 2 individuals, g_max generations, eta_mut = per-layer probability of a balanced +-1 move, seed of the
+ *   counter-based random stream (same arguments, same result, on any machine);
+ *   k_out: int32[L] receives k*; phi_out: NULL or receives phi(k*).
+ *   The reading of the steps the paper leaves open (tournaments of two, uniform crossover, balanced mutation, greedy
+ *   projection, elitist truncation to n_pop) is written out at the top of csrc/stage2.hip.
+ *   Returns LEXI_ERR_BAD_K when no feasible vector exists (B outside L*k_min .. L*k_max). */
+lexi_status lexi_allocate_topk(const double* D, int32_t L, int32_t B, int32_t k_min, int32_t k_max, int32_t n_pop,
+                               int32_t g_max, double eta_mut, uint64_t seed, int32_t* k_out, double* phi_out);
+
 /* Device ceilings for the roofline report (not part of the MoE path; the caller times the launches with events).
  *   lexi_probe_mfma_bf16: `workgroups` workgroups of 4 waves, each wave issuing iters * 16 independent
  *     v_mfma_f32_32x32x16_bf16 (32768 flops each) on operand fragments read once from `operands` (device, at least

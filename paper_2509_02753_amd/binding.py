@@ -20,7 +20,7 @@ SHARED_NONE, SHARED_UNGATED, SHARED_SIGMOID = 0, 1, 2
 
 EXPORTS = ("lexi_pack_weights", "lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward",
            "lexi_moe_stack_forward_profiled", "lexi_moe_profile_workspace_bytes", "lexi_moe_profile_layer",
-           "lexi_probe_mfma_bf16", "lexi_probe_hbm_read", "lexi_strerror",
+           "lexi_allocate_topk", "lexi_probe_mfma_bf16", "lexi_probe_hbm_read", "lexi_strerror",
            "lexi_moe_version")
 N_STAGE_EVENTS = 6
 STAGE_NAMES = ("routing", "gate_up", "down", "shared", "combine")
@@ -72,6 +72,9 @@ def _load() -> ctypes.CDLL:
     lib.lexi_moe_profile_workspace_bytes.argtypes = [ctypes.POINTER(lexi_layer_t), i32, i32, i32]
     lib.lexi_moe_profile_layer.restype = i32
     lib.lexi_moe_profile_layer.argtypes = [ctypes.POINTER(lexi_layer_t), vp, i32, i32, ctypes.POINTER(i32), i32, vp, vp, sz, vp]
+    lib.lexi_allocate_topk.restype = i32
+    lib.lexi_allocate_topk.argtypes = [ctypes.POINTER(ctypes.c_double), i32, i32, i32, i32, i32, i32, ctypes.c_double,
+                                       ctypes.c_uint64, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
     lib.lexi_probe_mfma_bf16.restype = i32
     lib.lexi_probe_mfma_bf16.argtypes = [vp, vp, i32, i32, vp]
     lib.lexi_probe_hbm_read.restype = i32
@@ -247,6 +250,23 @@ def lexi_moe_profile_layer(layer: Layer, x: torch.Tensor, k_base: int, k_list: S
     if st != LEXI_OK:
         raise LexiError(st, "lexi_moe_profile_layer")
     return delta
+
+
+def lexi_allocate_topk(D, B: int, k_min: int, k_max: int, n_pop: int = 32, g_max: int = 500, eta_mut: float = 0.1,
+                       seed: int = 0):
+    """Stage 2 (Algorithm 2) on the host: D [L][k_max+1] losses -> (k* as a list of ints, phi(k*))."""
+    import numpy as np
+    D = np.ascontiguousarray(D, dtype=np.float64)
+    if D.ndim != 2 or D.shape[1] != k_max + 1:
+        raise ValueError("D must be [L][k_max + 1]")
+    L = int(D.shape[0])
+    out = (ctypes.c_int32 * L)()
+    phi = ctypes.c_double()
+    st = _lib.lexi_allocate_topk(D.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), L, int(B), int(k_min), int(k_max),
+                                 int(n_pop), int(g_max), float(eta_mut), int(seed), out, ctypes.byref(phi))
+    if st != LEXI_OK:
+        raise LexiError(st, "lexi_allocate_topk")
+    return list(out), phi.value
 
 
 def lexi_probe_mfma_bf16(operands: torch.Tensor, sink: torch.Tensor, iters: int, workgroups: int,

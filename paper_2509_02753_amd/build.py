@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblexi_moe.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "routing.hip", "ffn.hip", "ffn_stream.hip", "combine.hip", "profile.hip", "probe.hip"]
+SOURCES = ["api.hip", "routing.hip", "ffn.hip", "ffn_stream.hip", "combine.hip", "profile.hip", "probe.hip", "stage2.hip"]
 # -packed-fp32-ops off: scalar fp32 code must not be turned into v_pk_*_f32 instructions.
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
              "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

@@ -70,3 +70,41 @@ def test_profile_rejects_bad_arguments():
         P.lexi_moe_profile_layer(dl, x, 65, [1])
     with pytest.raises(P.LexiError):
         P.lexi_moe_profile_layer(dl, x, 8, [1], workspace=torch.empty(1024, dtype=torch.uint8, device="cuda:0"))
+
+
+def test_lexi_pipeline_weights_to_allocation_to_stack_forward():
+    """The whole LExI loop on a small synthetic stack: Stage 1 (Algorithm 1) fills D[layer][k] with the mean deviation
+    over a few random inputs, Stage 2 (Algorithm 2) turns it into a per-layer allocation under a budget, and the stack
+    forward runs with that allocation.  Checked: D matches the oracle's table, the allocation equals the oracle's
+    search on the same table, is feasible and no worse than the flat vector, and the forward pass accepts it."""
+    import torch
+    import paper_2509_02753_amd as P
+    from oracle import stage2 as O2
+    cfg = S.mini(S.C2, L=4, d=256, F=384)
+    T, kb, n_iter = 96, cfg.k_base, 3
+    klist = list(range(1, kb + 1))
+    pairs = [device_and_host_layer(cfg, l) for l in range(cfg.L)]
+    D = np.zeros((cfg.L, kb + 1))
+    D_ref = np.zeros_like(D)
+    for l, (dl, hl) in enumerate(pairs):
+        for it in range(n_iter):
+            tid = S.tensor_id(l, S.KIND_X) + 1000 * (it + 1)          # a fresh X ~ N(0,1) per iteration
+            xd = torch.empty((T, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+            S.fill_device(xd, cfg.seed, tid, 1.0)
+            xh = S.fill_host(cfg.seed, tid, T * cfg.d, 1.0, cfg.dtype).reshape(T, cfg.d)
+            D[l, 1:] += P.lexi_moe_profile_layer(dl, xd, kb, klist).cpu().numpy() / n_iter
+            D_ref[l, 1:] += O.profile_layer(hl, xh, kb, klist, round_act=True) / n_iter
+    assert np.all(np.abs(D - D_ref) <= TOL * D_ref + 1e-9)
+    assert np.all(np.diff(D[:, 1:], axis=1) < 0)                       # fewer dropped experts, smaller deviation
+    B = cfg.L * kb * 3 // 4
+    k_star, phi = P.lexi_allocate_topk(D, B, 1, kb, n_pop=24, g_max=300, eta_mut=0.1, seed=9)
+    k_ref, _ = O2.allocate_topk(D, B, 1, kb, 24, 300, 0.1, seed=9)
+    assert k_star == k_ref.tolist() and sum(k_star) == B
+    flat = [B // cfg.L + (1 if j < B % cfg.L else 0) for j in range(cfg.L)]
+    assert phi <= O2.fitness(D, flat) + 1e-12
+    dls = [p[0] for p in pairs]
+    x = torch.stack([S.device_x(cfg, l, T) for l in range(cfg.L)])
+    y = torch.empty((cfg.L, T, cfg.d), dtype=torch.float32, device="cuda:0")
+    P.lexi_moe_stack_forward(dls, k_star, x, y, P.alloc_workspace(dls, T, max(k_star)))
+    torch.cuda.synchronize()
+    assert torch.isfinite(y).all()

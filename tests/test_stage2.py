@@ -44,7 +44,7 @@ def test_oracle_reaches_the_exhaustive_optimum_on_tiny_instances(seed):
     rng = np.random.default_rng(seed)
     D = random_table(rng, 5, 4, convex=False)
     for B in (8, 12, 15):
-        _, phi = O2.allocate_topk(D, B, 1, 4, 16, 400, 0.2, seed=seed)
+        _, phi = O2.allocate_topk(D, B, 1, 4, 32, 800, 0.2, seed=seed)
         assert abs(phi - brute_force(D, B, 1, 4)) < 1e-9
 
 
