@@ -224,3 +224,50 @@ def profile_layer(layer: Layer, x, k_base: int, k_list, round_act: bool = False)
         y_k = moe_layer(layer, x, int(k), round_act=round_act).out
         deltas[i] = np.sqrt(np.sum((y_k - y_base) ** 2))
     return deltas
+
+
+# ---------------------------------------------------------------- chained residual stack (pre-norm MoE blocks)
+RMS_EPS = 1e-6
+
+
+def bf16_rne(a: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding of float values to bf16, returned as uint16 bit patterns (finite inputs)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    u = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (u >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_to_f64(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def rms_norm(h: np.ndarray) -> np.ndarray:
+    """u = h / sqrt(mean_j(h_j^2) + eps) per token, fp64 (no learned scale)."""
+    h = np.asarray(h, dtype=np.float64)
+    return h / np.sqrt(np.mean(h * h, axis=1, keepdims=True) + RMS_EPS)
+
+
+def chained_layer(layer: Layer, h, k: int, u_forced=None, round_act: bool = True):
+    """One block of the chained stack: u = round_to_layer_dtype(rms_norm(h)), h' = h + f_moe(u; k).
+    h: [T][d] fp64/fp32 hidden state.  u_forced: if given (bf16 bit patterns or fp32 values), it is used as the MoE
+    input instead of the rounded normalisation (teacher forcing: lets a second implementation be checked block by
+    block on bit-identical MoE inputs).  Returns (h', u, LayerResult)."""
+    h = np.asarray(h, dtype=np.float64)
+    if u_forced is not None:
+        u = u_forced
+    elif layer.dtype == "bf16":
+        u = bf16_rne(rms_norm(h))
+    else:
+        u = rms_norm(h).astype(np.float32)
+    res = moe_layer(layer, u, k, round_act=round_act and layer.dtype == "bf16")
+    return h + res.out, u, res
+
+
+def chained_stack(layers, x, k_vec, round_act: bool = True):
+    """h_0 = x (widened exactly); h_{l+1} = h_l + f_moe_l(norm(h_l); k_l).  Returns the list [h_1 .. h_L] (fp64)."""
+    h = bf16_to_f64(x) if layers[0].dtype == "bf16" else np.asarray(x, dtype=np.float64)
+    hs = []
+    for l, ly in enumerate(layers):
+        h, _, _ = chained_layer(ly, h, int(k_vec[l]), round_act=round_act)
+        hs.append(h)
+    return hs

@@ -425,3 +425,41 @@ def test_profile_delta_matches_the_closed_form_in_the_dropped_experts():
             diff = sum((gk[s] - gb[s]) * O.expert_ffn(ly, int(sel[s]), x, t) for s in range(kb))
             total += float(np.sum(diff ** 2))
         assert abs(got[i] - np.sqrt(total)) <= 1e-6 * np.sqrt(total)   # the oracle stores its gates in fp32
+
+
+# ---------------------------------------------------------------- chained residual stack
+def test_bf16_rounding_helper_matches_exhaustive_definition():
+    """bf16_rne against the definition (nearest representable, ties to even mantissa) on values around boundaries."""
+    vals = np.array([1.0, 1.00390625, 1.0078125, 1.01171875, 1.005859375, -2.5, 3.1415927, 1e-20, 65504.0], dtype=np.float32)
+    got = O.bf16_to_f64(O.bf16_rne(vals))
+    for v, g in zip(vals.astype(np.float64), got):
+        lo = np.float32(v).view(np.uint32) & np.uint32(0xFFFF0000)
+        c0 = float(np.uint32(lo).view(np.float32))
+        c1 = float(np.uint32(lo + np.uint32(0x10000)).view(np.float32))
+        best = min((abs(v - c0), (lo >> 16) & 1, c0), (abs(v - c1), ((lo >> 16) + 1) & 1, c1))[2]
+        assert g == best
+
+
+def test_chained_stack_special_cases():
+    """Zero down-projections leave the hidden state untouched; one layer equals x + f(norm(x)); the normalised input
+    has unit mean square."""
+    rng = np.random.default_rng(31)
+    x = rng.normal(0, 3.0, (6, 128)).astype(np.float32)
+    ly = _tiny_layer(rng)
+    u = O.rms_norm(x)
+    assert np.allclose(np.mean(u * u, axis=1), 1.0, atol=1e-6)
+    hs = O.chained_stack([ly], x, [3])
+    direct = x.astype(np.float64) + O.moe_layer(ly, u.astype(np.float32), 3).out
+    assert np.array_equal(hs[0], direct)
+    zero = O.Layer(128, 6, 64, "f32", ly.w_router, ly.w_gate, ly.w_up, np.zeros_like(ly.w_down))
+    hs = O.chained_stack([zero, zero, zero], x, [1, 2, 3])
+    assert np.array_equal(hs[-1], x.astype(np.float64))
+
+
+def test_chained_layer_teacher_forcing_uses_the_given_input():
+    rng = np.random.default_rng(32)
+    x = rng.normal(0, 1.0, (5, 128)).astype(np.float32)
+    ly = _tiny_layer(rng)
+    forced = rng.normal(0, 1.0, (5, 128)).astype(np.float32)
+    h1, u, res = O.chained_layer(ly, x, 2, u_forced=forced)
+    assert u is forced and np.array_equal(h1, x.astype(np.float64) + O.moe_layer(ly, forced, 2).out)
