@@ -173,6 +173,7 @@ def main():
     ap.add_argument("--no-uniform", action="store_true", help="skip the uniform-k comparison run (profiling: every launch then uses k_vec)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
     ap.add_argument("--no-stage1", action="store_true", help="skip the Stage-1 profiling timing")
+    ap.add_argument("--no-chained", action="store_true", help="skip the timing of the chained residual mode")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the matrix-core / HBM ceiling probes")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="end with one 256 MiB device-to-device copy kernel (counter runs scale FETCH_SIZE / WRITE_SIZE by it)")
@@ -221,28 +222,31 @@ def main():
     from paper_2509_02753_amd.binding import _layer_array
     arr = _layer_array(layers)
 
-    def run_steps(kv, n, events=None):
+    def run_steps(kv, n, events=None, chained=False):
         for _ in range(n):
-            P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr, stage_events=events)
+            if chained:   # one input, hidden state updated in place in y[0]
+                P.lexi_moe_stack_forward(layers, kv, x[0], y[0], ws, layer_array=arr, chained=True)
+            else:
+                P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr, stage_events=events)
 
     prefill = (T * float(np.mean(kvec)) / cfg.E) >= 64
     use_graph = args.graph == "on" or (args.graph == "auto" and not prefill)
 
-    def captured(kv):
+    def captured(kv, chained=False):
         """The whole stack call (every launch of all L layers, the side-stream fork/join included) as one HIP graph."""
-        run_steps(kv, 1)                       # first-use set-up inside the library happens outside the capture
+        run_steps(kv, 1, chained=chained)      # first-use set-up inside the library happens outside the capture
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr)
+            run_steps(kv, 1, chained=chained)
         return g
 
-    def timed(kv):
+    def timed(kv, chained=False):
         if use_graph:
-            g = captured(kv)
+            g = captured(kv, chained)
             step = g.replay
         else:
-            step = lambda: run_steps(kv, 1)
+            step = lambda: run_steps(kv, 1, chained=chained)
         for _ in range(args.warmup):
             step()
         torch.cuda.synchronize()
@@ -258,6 +262,14 @@ def main():
     sec_uniform = timed(kuni) if compare_uniform else None
     if compare_uniform:
         log(f"[bench] uniform k={cfg.k_base}: {sec_uniform * 1e3:.3f} ms/step, {T / sec_uniform:,.0f} tokens/s")
+
+    # chained residual mode (pre-norm blocks, fp32 hidden state): same layers and k vector, one input
+    chained = None
+    if not args.no_chained and len({(ly.c.d, ly.c.dtype) for ly in layers}) == 1:
+        sec_ch = timed(kvec, chained=True)
+        chained = {"ms_per_step": round(sec_ch * 1e3, 4), "tokens_per_s": round(T / sec_ch, 1),
+                   "vs_independent": round(sec / sec_ch, 4)}
+        log(f"[bench] chained residual mode: {sec_ch * 1e3:.3f} ms/step, {T / sec_ch:,.0f} tokens/s")
 
     # ---- per-stage durations with HIP events recorded by the library on the launch stream ----
     ev = P.StageEvents(L)
@@ -391,7 +403,7 @@ def main():
         "uniform_k_tokens_per_s": round(T / sec_uniform, 1) if sec_uniform else None,
         "speedup_vs_uniform_k": round(sec_uniform / sec, 4) if sec_uniform else None,
         "stage_ms_per_step": {n: round(float(v), 4) for n, v in zip(P.STAGE_NAMES, per_stage)},
-        "roofline": roofline, "whole_path": whole, "measured_ceilings": ceilings, "stage1_profiling": stage1,
+        "chained_stack": chained, "roofline": roofline, "whole_path": whole, "measured_ceilings": ceilings, "stage1_profiling": stage1,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -102,7 +102,12 @@ typedef struct {
     int32_t* offsets;   /* [E+1]   exclusive scan of counts */
     int32_t* perm;      /* [T*k]   position -> assignment t*k+s */
     int32_t* inv_perm;  /* [T*k]   assignment -> position */
+    void* moe_input;    /* [T][d]  of the layer dtype: the input the MoE block actually consumed (a copy of x; in the
+                           chained mode the normalised hidden state) */
 } lexi_routing_out_t;
+
+/* Stack modes. */
+typedef enum { LEXI_STACK_INDEPENDENT = 0, LEXI_STACK_CHAINED = 1 } lexi_stack_mode;
 
 /* Re-layout of expert weights (the E_i of Sec. 2) from row-major into the packed layout described above.
  *   src: device, n_matrices row-major matrices [rows][K] back to back; dst: device, same size, must not overlap src;
@@ -124,8 +129,12 @@ lexi_status lexi_moe_layer_forward(const lexi_layer_t* layer, const void* x, voi
 
 /* A stack of L layers with the static per-layer allocation k_vec = (k_1 .. k_L) (Sec. 1; output of Algorithm 2).
  *   layers: host array[L]; k_vec: HOST int32[L].
- *   mode 0 (the only one): layer l reads x + l*x_layer_stride elements and writes y + l*y_layer_stride elements
+ *   mode LEXI_STACK_INDEPENDENT: layer l reads x + l*x_layer_stride elements and writes y + l*y_layer_stride elements
  *   (stride 0 for x = every layer reads the same X, as in Algorithm 1's per-layer profiling on one random X).
+ *   mode LEXI_STACK_CHAINED: pre-norm residual blocks, the setting of end-to-end inference (Sec. 3) reduced to its
+ *   MoE blocks: h_0 = x [T][d] (x_layer_stride must be 0);  u_l = h_l / sqrt(mean_j h_l[j]^2 + 1e-6) rounded to the
+ *   layer dtype;  h_{l+1} = h_l + f_moe_l(u_l; k_l), hidden state in fp32 (y_dtype must be LEXI_F32).  y + l*
+ *   y_layer_stride receives h_{l+1}; stride 0 keeps only the final hidden state.  All layers share d and dtype.
  *   dbg_per_layer: NULL or host array[L]. */
 lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const int32_t* k_vec, const void* x,
                                    int64_t x_layer_stride, void* y, int64_t y_layer_stride, int32_t y_dtype,

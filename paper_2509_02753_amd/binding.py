@@ -43,7 +43,8 @@ class lexi_layer_t(ctypes.Structure):
 
 class lexi_routing_out_t(ctypes.Structure):
     _fields_ = [("topk_idx", ctypes.c_void_p), ("gates", ctypes.c_void_p), ("counts", ctypes.c_void_p),
-                ("offsets", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("inv_perm", ctypes.c_void_p)]
+                ("offsets", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("inv_perm", ctypes.c_void_p),
+                ("moe_input", ctypes.c_void_p)]
 
 
 class lexi_stage_events_t(ctypes.Structure):
@@ -164,8 +165,9 @@ class Layer:
 class RoutingOut:
     """Device arrays that receive the routing decision of one layer call."""
 
-    def __init__(self, T: int, k: int, E: int, device="cuda:0"):
+    def __init__(self, T: int, k: int, E: int, device="cuda:0", moe_input: Optional[torch.Tensor] = None):
         i32 = dict(dtype=torch.int32, device=device)
+        self.moe_input = moe_input          # optional [T][d] tensor of the layer dtype
         self.topk_idx = torch.empty((T, k), **i32)
         self.gates = torch.empty((T, k), dtype=torch.float32, device=device)
         self.counts = torch.empty(E, **i32)
@@ -173,7 +175,7 @@ class RoutingOut:
         self.perm = torch.empty(T * k, **i32)
         self.inv_perm = torch.empty(T * k, **i32)
         self.c = lexi_routing_out_t(_dp(self.topk_idx), _dp(self.gates), _dp(self.counts), _dp(self.offsets),
-                                    _dp(self.perm), _dp(self.inv_perm))
+                                    _dp(self.perm), _dp(self.inv_perm), _dp(moe_input))
 
 
 def _layer_array(layers: Sequence[Layer]):
@@ -207,8 +209,10 @@ def lexi_moe_layer_forward(layer: Layer, x: torch.Tensor, y: torch.Tensor, k: in
 
 def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: torch.Tensor, y: torch.Tensor,
                            workspace: torch.Tensor, routing: Optional[Sequence[RoutingOut]] = None,
-                           stream: Optional[torch.cuda.Stream] = None, layer_array=None, stage_events=None) -> None:
+                           stream: Optional[torch.cuda.Stream] = None, layer_array=None, stage_events=None,
+                           chained: bool = False) -> None:
     """Stack of L layers with the per-layer k vector.  x: [T][d] (shared by all layers) or [L][T][d]; y: [L][T][d].
+    chained=True: pre-norm residual blocks h_{l+1} = h_l + f_l(norm(h_l)); x [T][d], y fp32 [L][T][d] or [T][d].
 
     stage_events: None, or a StageEvents object; then the profiled entry point records its events."""
     L = len(layers)
@@ -224,11 +228,11 @@ def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: tor
     arr = layer_array if layer_array is not None else _layer_array(layers)
     if stage_events is not None:
         st = _lib.lexi_moe_stack_forward_profiled(arr, L, kv, _dp(x), x_stride, _dp(y), y_stride, _dtype_code(y.dtype),
-                                                  T, 0, _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg,
+                                                  T, int(chained), _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg,
                                                   stage_events.c)
     else:
-        st = _lib.lexi_moe_stack_forward(arr, L, kv, _dp(x), x_stride, _dp(y), y_stride, _dtype_code(y.dtype), T, 0,
-                                         _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg)
+        st = _lib.lexi_moe_stack_forward(arr, L, kv, _dp(x), x_stride, _dp(y), y_stride, _dtype_code(y.dtype), T,
+                                         int(chained), _dp(workspace), workspace.numel(), _stream_ptr(stream), dbg)
     if st != LEXI_OK:
         raise LexiError(st, "lexi_moe_stack_forward")
 

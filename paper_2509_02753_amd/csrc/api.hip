@@ -61,7 +61,7 @@ struct Carver {
 struct Workspace {
     int32_t *topk_idx, *local_rank, *blk_hist, *counts, *offsets, *perm, *inv_perm, *row_token, *sched, *sched_count;
     float *gates, *partial, *y_slot, *y_shared;
-    void *act, *act_shared;
+    void *act, *act_shared, *u;
     int max_tiles;
     size_t bytes;
 };
@@ -92,6 +92,7 @@ Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
         w.act_shared = c.take<char>((size_t)T * ly.F_shared * es);
         w.y_shared = c.take<float>((size_t)T * ly.d);
     }
+    w.u = c.take<char>((size_t)T * ly.d * es);   // chained stack: the normalised MoE input
     w.bytes = align_up(c.used, 256);
     return w;
 }
@@ -129,7 +130,7 @@ lexi_status check_call(const lexi_layer_t* ly, const void* x, const void* y, int
     if (!x || !y || !workspace) return LEXI_ERR_NULL;
     if (misaligned(x) || misaligned(y) || misaligned(workspace)) return LEXI_ERR_ALIGN;
     if (dbg) {
-        const void* ptrs[] = {dbg->topk_idx, dbg->gates, dbg->counts, dbg->offsets, dbg->perm, dbg->inv_perm};
+        const void* ptrs[] = {dbg->topk_idx, dbg->gates, dbg->counts, dbg->offsets, dbg->perm, dbg->inv_perm, dbg->moe_input};
         for (const void* p : ptrs)
             if (p && misaligned(p)) return LEXI_ERR_ALIGN;
     }
@@ -176,15 +177,25 @@ lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t
 }
 
 // One layer, arguments already validated.
+// `hidden` != null selects the chained block: x is ignored, the MoE input is the normalised hidden state and the
+// block's output is added to it (y may be `hidden` itself).
 lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_dtype, int32_t T, int32_t k,
                       void* workspace, hipStream_t s, const lexi_routing_out_t* dbg,
-                      const lexi_stage_events_t* events = nullptr) {
+                      const lexi_stage_events_t* events = nullptr, const float* hidden = nullptr) {
     auto mark = [&](int i) {
         if (events && events->ev[i]) (void)hipEventRecord((hipEvent_t)events->ev[i], s);
     };
     mark(0);
     Workspace w = carve(ly, T, k, workspace);
     const bool bf = ly.dtype == LEXI_BF16;
+    if (hidden != nullptr) {
+        void* u = (dbg && dbg->moe_input) ? dbg->moe_input : w.u;
+        if (launch_rmsnorm(hidden, T, ly.d, kRmsEps, u, bf, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+        x = u;
+    } else if (dbg && dbg->moe_input) {
+        if (hipMemcpyAsync(dbg->moe_input, x, (size_t)T * ly.d * (bf ? 2 : 4), hipMemcpyDeviceToDevice, s) != hipSuccess)
+            return LEXI_ERR_LAUNCH;
+    }
     // routing results land directly in the caller's arrays when those are given
     if (dbg) {
         if (dbg->topk_idx) w.topk_idx = dbg->topk_idx;
@@ -241,6 +252,7 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     c.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr;
     c.x = x; c.x_bf16 = bf;
     c.w_shared_gate = ly.shared_kind == LEXI_SHARED_SIGMOID ? ly.w_shared_gate : nullptr;
+    c.residual = hidden;
     c.T = T; c.d = ly.d; c.k = k; c.y = y; c.y_bf16 = y_dtype == LEXI_BF16;
     if (launch_combine(c, s) != hipSuccess) return LEXI_ERR_LAUNCH;
     mark(5);
@@ -294,7 +306,9 @@ lexi_status lexi_moe_stack_forward_profiled(const lexi_layer_t* layers, int32_t 
                                             const lexi_stage_events_t* events_per_layer) {
     if (!layers || !k_vec) return LEXI_ERR_NULL;
     if (L < 1 || x_layer_stride < 0 || y_layer_stride < 0) return LEXI_ERR_SHAPE;
-    if (mode != 0) return LEXI_ERR_DTYPE;
+    if (mode != LEXI_STACK_INDEPENDENT && mode != LEXI_STACK_CHAINED) return LEXI_ERR_DTYPE;
+    const bool chained = mode == LEXI_STACK_CHAINED;
+    if (chained && (y_dtype != LEXI_F32 || x_layer_stride != 0)) return LEXI_ERR_DTYPE;   // fp32 hidden state, one input
     // validate every layer before the first launch: an error must leave nothing enqueued
     for (int l = 0; l < L; ++l) {
         const size_t xes = layers[l].dtype == LEXI_BF16 ? 2 : 4;
@@ -304,15 +318,38 @@ lexi_status lexi_moe_stack_forward_profiled(const lexi_layer_t* layers, int32_t 
         lexi_status st = check_call(&layers[l], xl, yl, y_dtype, T, k_vec[l], workspace, workspace_bytes,
                                     dbg_per_layer ? &dbg_per_layer[l] : nullptr);
         if (st != LEXI_OK) return st;
-        if (L > 1 && T > 0 && y_layer_stride < (int64_t)T * layers[l].d) return LEXI_ERR_SHAPE;  // outputs would overlap
+        if (chained) {
+            // one hidden state flows through all blocks: same width and dtype everywhere; outputs either all in one
+            // buffer (stride 0: only the last survives) or one full buffer per layer
+            if (layers[l].d != layers[0].d || layers[l].dtype != layers[0].dtype) return LEXI_ERR_SHAPE;
+            if (y_layer_stride != 0 && y_layer_stride < (int64_t)T * layers[l].d) return LEXI_ERR_SHAPE;
+        } else if (L > 1 && T > 0 && y_layer_stride < (int64_t)T * layers[l].d) {
+            return LEXI_ERR_SHAPE;  // outputs would overlap
+        }
     }
     if (T == 0) return LEXI_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (chained) {
+        // h_0 = x, widened into the first output buffer; block l reads h_l where block l-1 left it and writes h_{l+1}
+        float* h = (float*)y;
+        if (launch_widen(x, layers[0].dtype == LEXI_BF16, (size_t)T * layers[0].d, h, s) != hipSuccess)
+            return LEXI_ERR_LAUNCH;
+        for (int l = 0; l < L; ++l) {
+            float* h_out = (float*)y + (size_t)l * y_layer_stride;
+            lexi_status st = run_layer(layers[l], nullptr, h_out, LEXI_F32, T, k_vec[l], workspace, s,
+                                       dbg_per_layer ? &dbg_per_layer[l] : nullptr,
+                                       events_per_layer ? &events_per_layer[l] : nullptr, h);
+            if (st != LEXI_OK) return st;
+            h = h_out;
+        }
+        return LEXI_OK;
+    }
     for (int l = 0; l < L; ++l) {
         const size_t xes = layers[l].dtype == LEXI_BF16 ? 2 : 4;
         const size_t yes = y_dtype == LEXI_BF16 ? 2 : 4;
         const void* xl = (const char*)x + (size_t)l * x_layer_stride * xes;
         void* yl = (char*)y + (size_t)l * y_layer_stride * yes;
-        lexi_status st = run_layer(layers[l], xl, yl, y_dtype, T, k_vec[l], workspace, (hipStream_t)hip_stream,
+        lexi_status st = run_layer(layers[l], xl, yl, y_dtype, T, k_vec[l], workspace, s,
                                    dbg_per_layer ? &dbg_per_layer[l] : nullptr,
                                    events_per_layer ? &events_per_layer[l] : nullptr);
         if (st != LEXI_OK) return st;

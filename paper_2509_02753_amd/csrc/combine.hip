@@ -11,7 +11,7 @@ template <bool Y_BF16, bool X_BF16>
 __global__ void __launch_bounds__(256)
 combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv_perm, const float* __restrict__ gates,
                const float* __restrict__ y_shared, const void* __restrict__ x, const void* __restrict__ w_shared_gate,
-               int d, int k, void* __restrict__ y) {
+               const float* residual, int d, int k, void* y) {
     __shared__ float wave_part[4];
     const int t = blockIdx.x;
     const int32_t* ip = inv_perm + (size_t)t * k;
@@ -40,6 +40,11 @@ combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[i] = __builtin_fmaf(coef, v[i], acc[i]);
         }
+        if (residual != nullptr) {   // chained stack: the hidden state plus this block's output (may alias y: same element)
+            const f32x4_t h = *(const f32x4_t*)(residual + (size_t)t * d + j);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = h[i] + acc[i];
+        }
         if (Y_BF16) {
             u32x2_t pk;
             pk[0] = pack_bf16x2(acc[0], acc[1]);
@@ -54,7 +59,64 @@ combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv
 template <bool Y_BF16, bool X_BF16>
 static void launch_combine_t(const CombineArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((combine_kernel<Y_BF16, X_BF16>), dim3(a.T), dim3(256), 0, s, a.y_slot, a.inv_perm, a.gates,
-                       a.y_shared, a.x, a.w_shared_gate, a.d, a.k, a.y);
+                       a.y_shared, a.x, a.w_shared_gate, a.residual, a.d, a.k, a.y);
+}
+
+// Chained stack: u[t] = h[t] / sqrt(mean_j h[t][j]^2 + eps), rounded to the layer dtype.  One workgroup per token;
+// the sum of squares in a fixed order (per-thread strided fused multiply-adds, DPP tree, the four waves in order).
+template <bool U_BF16>
+__global__ void __launch_bounds__(256)
+rmsnorm_kernel(const float* __restrict__ h, int d, float eps, void* __restrict__ u) {
+    __shared__ float wave_part[4];
+    const int t = blockIdx.x;
+    const float* ht = h + (size_t)t * d;
+    // d % 128 == 0 (checked at the boundary): 16-byte pieces, thread-strided
+    float ss = 0.0f;
+    for (int j = threadIdx.x * 4; j < d; j += 1024) {
+        const f32x4_t v = *(const f32x4_t*)(ht + j);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(v[i], v[i], ss);
+    }
+    const float ws = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = ws;
+    __syncthreads();
+    const float total = ((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3];
+    const float inv = 1.0f / sqrtf(total / (float)d + eps);
+    for (int j = threadIdx.x * 4; j < d; j += 1024) {
+        const f32x4_t v = *(const f32x4_t*)(ht + j);   // second read of the row: served by the cache
+        if (U_BF16) {
+            u32x2_t pk;
+            pk[0] = (uint32_t)f32_to_bf16(v[0] * inv) | ((uint32_t)f32_to_bf16(v[1] * inv) << 16);
+            pk[1] = (uint32_t)f32_to_bf16(v[2] * inv) | ((uint32_t)f32_to_bf16(v[3] * inv) << 16);
+            *(u32x2_t*)((bf16_t*)u + (size_t)t * d + j) = pk;
+        } else {
+            f32x4_t o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = v[i] * inv;
+            *(f32x4_t*)((float*)u + (size_t)t * d + j) = o;
+        }
+    }
+}
+
+// h = x widened exactly to fp32 (the chained stack's hidden state starts as the input).
+template <bool X_BF16>
+__global__ void __launch_bounds__(256)
+widen_kernel(const void* __restrict__ x, size_t n, float* __restrict__ h) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) h[i] = load_as_f32<X_BF16>(x, i);
+}
+
+hipError_t launch_rmsnorm(const float* h, int T, int d, float eps, void* u, bool u_bf16, hipStream_t s) {
+    if (u_bf16) hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(T), dim3(256), 0, s, h, d, eps, u);
+    else hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(T), dim3(256), 0, s, h, d, eps, u);
+    return hipGetLastError();
+}
+
+hipError_t launch_widen(const void* x, bool x_bf16, size_t n, float* h, hipStream_t s) {
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (x_bf16) hipLaunchKernelGGL(widen_kernel<true>, dim3(blocks), dim3(256), 0, s, x, n, h);
+    else hipLaunchKernelGGL(widen_kernel<false>, dim3(blocks), dim3(256), 0, s, x, n, h);
+    return hipGetLastError();
 }
 
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s) {

@@ -65,10 +65,16 @@ struct CombineArgs {
     const void* w_shared_gate; // [d] or null (ungated: coefficient 1)
     bool x_bf16;
     int T, d, k;
+    const float* residual;     // [T][d] fp32 added to the result (chained stack), or null; may alias y
     void* y;                   // [T][d]
     bool y_bf16;
 };
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+
+// chained stack: normalised MoE input u (layer dtype) from the fp32 hidden state h; h = widened x
+constexpr float kRmsEps = 1e-6f;
+hipError_t launch_rmsnorm(const float* h, int T, int d, float eps, void* u, bool u_bf16, hipStream_t s);
+hipError_t launch_widen(const void* x, bool x_bf16, size_t n, float* h, hipStream_t s);
 
 // Stage-1 profiling: squared-difference reduction over the slot rows of one baseline pass.
 constexpr int kProfileMaxK = 64;

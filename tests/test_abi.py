@@ -76,7 +76,11 @@ def test_workspace_query_is_monotone_and_checked():
     st = _lib.lexi_moe_stack_forward(arr, 2, kv, 0x50000, 0, 0x60000, 64 * 256, 0, 64, 0, 0x70000, 1 << 40, None, None)
     assert st == -3
     kv = (ctypes.c_int32 * 2)(2, 2)
-    assert _lib.lexi_moe_stack_forward(arr, 2, kv, 0x50000, 0, 0x60000, 64 * 256, 0, 64, 1, 0x70000, 1 << 40, None, None) == -4
+    call = lambda y_dtype, x_stride, mode: _lib.lexi_moe_stack_forward(
+        arr, 2, kv, 0x50000, x_stride, 0x60000, 64 * 256, y_dtype, 64, mode, 0x70000, 1 << 40, None, None)
+    assert call(0, 0, 2) == -4                       # unknown mode
+    assert call(1, 0, 1) == -4                       # chained mode keeps the hidden state in fp32
+    assert call(0, 64 * 256, 1) == -4                # chained mode has one input
     assert _lib.lexi_moe_stack_forward(arr, 2, kv, 0x50000, 0, 0x60000, 10, 0, 64, 0, 0x70000, 1 << 40, None, None) == -2
     assert _lib.lexi_moe_stack_forward(arr, 2, None, 0x50000, 0, 0x60000, 64 * 256, 0, 64, 0, 0x70000, 1 << 40, None, None) == -1
 
