@@ -448,7 +448,7 @@ def test_chained_stack_special_cases():
     ly = _tiny_layer(rng)
     u = O.rms_norm(x)
     assert np.allclose(np.mean(u * u, axis=1), 1.0, atol=1e-6)
-    assert np.allclose(O.rms_norm(1000.0 * x), u, rtol=0, atol=1e-9)          # scale-invariant up to the epsilon
+    assert np.allclose(O.rms_norm(1000.0 * x), u, rtol=0, atol=1e-6)          # scale-invariant up to the epsilon
     hand = O.rms_norm(np.array([[3.0, -4.0, 0.0, 0.0]]))                       # mean square 25/4
     assert np.allclose(hand, np.array([[3.0, -4.0, 0.0, 0.0]]) / np.sqrt(6.25 + 1e-6), rtol=1e-15)
     assert abs(hand[0, 0] - 1.2) < 1e-6 and abs(hand[0, 1] + 1.6) < 1e-6
