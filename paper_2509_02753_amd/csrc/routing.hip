@@ -288,11 +288,19 @@ scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, in
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int chunk = (nblk + 15) / 16;
     const int b0 = wave * chunk, b1 = min(nblk, b0 + chunk);
+    // the chunk's histograms are loaded eight at a time (independent loads in flight), then prefixed in order
     int32_t running = 0;
-    for (int b = b0; b < b1; ++b) {
-        const int32_t h = blk_hist[(size_t)b * 64 + lane];
-        blk_hist[(size_t)b * 64 + lane] = running;
-        running += h;
+    for (int b = b0; b < b1; b += 8) {
+        int32_t h[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) h[u] = blk_hist[(size_t)min(b + u, b1 - 1) * 64 + lane];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (b + u < b1) {
+                blk_hist[(size_t)(b + u) * 64 + lane] = running;
+                running += h[u];
+            }
+        }
     }
     chunk_tot[wave][lane] = running;
     __syncthreads();
@@ -303,8 +311,16 @@ scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, in
         base += (w < wave) ? c : 0;
         total += c;
     }
-    if (base != 0)
-        for (int b = b0; b < b1; ++b) blk_hist[(size_t)b * 64 + lane] += base;
+    if (base != 0) {
+        for (int b = b0; b < b1; b += 8) {
+            int32_t h[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) h[u] = blk_hist[(size_t)min(b + u, b1 - 1) * 64 + lane];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (b + u < b1) blk_hist[(size_t)(b + u) * 64 + lane] = h[u] + base;
+        }
+    }
     const int32_t ntile = (total + tile_tokens - 1) / tile_tokens;
     if (wave == 0) {
         s_cnt[lane] = total;
@@ -347,6 +363,118 @@ scan_kernel(int32_t* __restrict__ blk_hist, int nblk, int E, int tile_tokens, in
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// topk_scan_kernel (decode-sized batches, T <= kFusedTailMaxT): ONE workgroup of 16 waves does everything after the
+// segment partials -- the top-k and gates of every token (one token per wave per pass, tokens ascending), the
+// per-expert counts, offsets and tile schedule, and the scatter.  With all tokens in one workgroup the stable
+// counting sort needs no block histograms in memory: an assignment's position is offsets[e] + (assignments to e by
+// earlier tokens), kept in LDS.  Saves two dependent launches on the latency-bound path.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kFusedTailMaxT = 16;
+constexpr int kFusedTailMaxA = kFusedTailMaxT * 64;   // assignments (k <= E <= 64)
+
+__global__ void __launch_bounds__(1024)
+topk_scan_kernel(const float* __restrict__ partial, const float* __restrict__ bias, int T, int nseg, int E, int k,
+                 int tile_tokens, int32_t* __restrict__ topk_idx, float* __restrict__ gates,
+                 int32_t* __restrict__ counts, int32_t* __restrict__ offsets, int32_t* __restrict__ sched,
+                 int32_t* __restrict__ sched_count, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+                 int32_t* __restrict__ row_token) {
+    __shared__ int32_t wave_hit[16][64];        // this pass: 1 if the wave's token selected expert e
+    __shared__ int32_t s_seen[64];              // assignments to expert e by the tokens of earlier passes
+    __shared__ int32_t s_tiles[64];
+    __shared__ int32_t s_off[64];
+    __shared__ uint8_t s_e[kFusedTailMaxA];     // expert of assignment a
+    __shared__ int16_t s_rank[kFusedTailMaxA];  // assignments to that expert by earlier tokens
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool lane_valid = lane < E;
+    if (wave == 0) s_seen[lane] = 0;
+    const float b = (bias != nullptr && lane_valid) ? bias[lane] : 0.0f;
+    __syncthreads();
+    for (int t0 = 0; t0 < T; t0 += 16) {
+        const int t = t0 + wave;
+        const bool live = t < T;                // wave-uniform
+        int32_t sel = 0;
+        bool hit = false;
+        if (live) {
+            // logit = ordered sum of the segment partials, then the bias (same order as topk_kernel)
+            float total = partial[(size_t)t * 64 + lane];
+            for (int sg0 = 1; sg0 < nseg; sg0 += 8) {
+                float tmp[8];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) tmp[c] = partial[((size_t)min(sg0 + c, nseg - 1) * T + t) * 64 + lane];
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+                    if (sg0 + c < nseg) total = total + tmp[c];
+            }
+            if (bias != nullptr) total = total + b;
+            float val = -INFINITY;
+            for (int s = 0; s < k; ++s) {
+                const bool open = lane_valid && !hit;
+                const float mx = wave_max(open ? total : -INFINITY);
+                const uint64_t holders = __ballot(open && total == mx);
+                const int e_star = __builtin_ctzll(holders);   // lowest index among equal logits
+                if (lane == e_star) hit = true;
+                if (lane == s) { sel = e_star; val = mx; }
+            }
+            const float v0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(val), 0));
+            const float ex = (lane < k) ? __expf(val - v0) : 0.0f;
+            const float g = ex / wave_sum(ex);
+            if (lane < k) {
+                const size_t a = (size_t)t * k + lane;
+                topk_idx[a] = sel;
+                gates[a] = g;
+                s_e[a] = (uint8_t)sel;
+            }
+        }
+        wave_hit[wave][lane] = hit ? 1 : 0;
+        __syncthreads();
+        if (live && lane < k) {
+            int32_t before = s_seen[sel];
+            for (int w = 0; w < wave; ++w) before += wave_hit[w][sel];
+            s_rank[t * k + lane] = (int16_t)before;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            int32_t h = 0;
+#pragma unroll
+            for (int w = 0; w < 16; ++w) h += wave_hit[w][lane];
+            s_seen[lane] += h;
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+        const int32_t total = s_seen[lane];
+        const int32_t ntile = (total + tile_tokens - 1) / tile_tokens;
+        s_tiles[lane] = ntile;
+        __builtin_amdgcn_s_waitcnt(0);          // wave 0 reads what its own lanes wrote: order the LDS accesses
+        __builtin_amdgcn_wave_barrier();
+        int32_t off = 0, tile_base = 0;
+        for (int e = 0; e < lane; ++e) { off += s_seen[e]; tile_base += s_tiles[e]; }
+        s_off[lane] = off;
+        if (lane < E) {
+            counts[lane] = total;
+            offsets[lane] = off;
+            for (int i = 0; i < ntile; ++i) {
+                int32_t* sp = sched + (size_t)(tile_base + i) * 8;
+                sp[0] = lane; sp[1] = off; sp[2] = total; sp[3] = i; sp[4] = ntile;
+            }
+        }
+        if (lane == 63) {
+            offsets[E] = off + total;
+            sched_count[0] = tile_base + ntile;
+        }
+    }
+    __syncthreads();
+    const int A = T * k;
+    for (int a = threadIdx.x; a < A; a += 1024) {
+        const int pos = s_off[s_e[a]] + s_rank[a];
+        perm[pos] = a;
+        inv_perm[a] = pos;
+        row_token[pos] = a / k;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // permute_kernel: position of assignment a = offsets[e] + (assignments to e in earlier blocks) + rank in block.
 // ---------------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
@@ -371,7 +499,7 @@ permute_kernel(const int32_t* __restrict__ topk_idx, const int32_t* __restrict__
 constexpr int kTinyRouterMaxT = 128;    // at or below: one token per wave in the partial and top-k kernels
 constexpr int kSmallRouterMaxT = 1024;  // at or below this many tokens the latency-oriented partial kernel runs
 
-int router_tokens_per_block(int T) { return T >= 2048 ? 32 : 8; }
+int router_tokens_per_block(int T) { return T >= 2048 ? 16 : 8; }
 
 template <bool IS_BF16>
 static hipError_t launch_partials(const RoutingArgs& a, hipStream_t s) {
@@ -395,10 +523,16 @@ hipError_t launch_routing(const RoutingArgs& a, hipStream_t s) {
     hipError_t err = a.is_bf16 ? launch_partials<true>(a, s) : launch_partials<false>(a, s);
     if (err != hipSuccess) return err;
     const int nseg = a.d / kRouterSegment;
+    if (a.T <= kFusedTailMaxT) {
+        hipLaunchKernelGGL(topk_scan_kernel, dim3(1), dim3(1024), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
+                           a.tile_tokens, a.topk_idx, a.gates, a.counts, a.offsets, a.sched, a.sched_count, a.perm,
+                           a.inv_perm, a.row_token);
+        return hipGetLastError();
+    }
     const int tb = router_tokens_per_block(a.T);
     const int nblk = (a.T + tb - 1) / tb;
-    if (tb == 32)
-        hipLaunchKernelGGL((topk_kernel<8, 4>), dim3(nblk), dim3(256), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
+    if (tb == 16)
+        hipLaunchKernelGGL((topk_kernel<4, 4>), dim3(nblk), dim3(256), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,
                            a.topk_idx, a.gates, a.local_rank, a.blk_hist);
     else if (a.T <= kTinyRouterMaxT)
         hipLaunchKernelGGL((topk_kernel<1, 8>), dim3(nblk), dim3(512), 0, s, a.partial, a.bias, a.T, nseg, a.E, a.k,

@@ -20,6 +20,9 @@ def test_c1_plumbing_fp32_full_size():
     ("c3_qwen15", 700, 4), ("c3_qwen15", 64, 1), ("c3_qwen15", 37, 60),
     ("c4_mixtral", 700, 2), ("c4_mixtral", 32, 1), ("c4_mixtral", 513, 8),
     ("c5_dsv2lite", 1, 6), ("c5_dsv2lite", 16, 4), ("c5_dsv2lite", 256, 6), ("c5_dsv2lite", 1000, 2),
+    # around the batch sizes where the routing path switches kernels
+    ("c5_dsv2lite", 5, 6), ("c2_olmoe", 16, 64), ("c3_qwen15", 17, 4), ("c5_dsv2lite", 128, 3), ("c2_olmoe", 2047, 5),
+    ("c2_olmoe", 2100, 3),
 ])
 def test_mini_layers_all_tokens(name, T, k):
     """Scaled-down shapes (same E, k range, shared expert and bias as the workload), every token compared.
