@@ -14,12 +14,14 @@ namespace lexi {
 // prefill-sized T, a latency-oriented one for decode-sized T) and summed in order by topk_kernel.
 // ---------------------------------------------------------------------------------------------------------
 
-// router_partial_kernel: workgroup = 256 tokens x 64 experts x one segment, 4 waves.  A wave owns 64 tokens; a lane
-// owns an 8 (tokens) x 8 (experts) block of accumulators, so per j it reads 8 x-values and 8 w-values from LDS for 64
-// fused multiply-adds.  x is staged through LDS transposed ([j][token], fp32) by the thread that owns the token row,
-// W[j][e] row-major; the next 32-j stage is prefetched into registers while the current one is consumed.
+// router_partial_kernel: workgroup = 256 tokens x 64 experts x one segment, 8 waves.  A wave owns 64 tokens and one
+// half of the experts; a lane owns an 8 (tokens) x 4 (experts) block of accumulators, so per j it reads 8 x-values and
+// 4 w-values from LDS for 32 fused multiply-adds.  (Blocks of 8 x 8 with four waves leave one wave per SIMD, which
+// measured 45 % of the plain-FMA rate; two waves per SIMD fill each other's issue gaps.)  x is staged through LDS
+// transposed ([j][token], fp32) by the thread that owns the token row, W[j][e] row-major by the other four waves;
+// the next 32-j stage is prefetched into registers while the current one is consumed.
 template <bool IS_BF16>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(512)
 router_partial_kernel(const void* __restrict__ x, const float* __restrict__ w_router, int T, int d, int E,
                       float* __restrict__ partial) {
     constexpr int SJ = 32;                      // j per LDS stage
@@ -28,58 +30,66 @@ router_partial_kernel(const void* __restrict__ x, const float* __restrict__ w_ro
     __shared__ __attribute__((aligned(16))) float wsm[SJ][64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tw = wave & 3, eh = wave >> 2;    // token quarter, expert half
     const int eg = lane & 7, tg = lane >> 3;
     const int seg = blockIdx.y;
     const int tok_base = blockIdx.x * 256;
-    const int my_row = min(tok_base + tid, T - 1);  // rows past T re-read the last row; never stored
+    const bool x_loader = tid < 256;            // waves 0..3 stage x (one token row per thread), waves 4..7 stage W
+    const int my_row = min(tok_base + (tid & 255), T - 1);  // rows past T re-read the last row; never stored
     const int j_seg = seg * kRouterSegment;
 
     u32x4_t xr[IS_BF16 ? 4 : 8];
     float wr[8];
     auto load_stage = [&](int st) {
         const int j0 = j_seg + st * SJ;
-        if (IS_BF16) {
-            const u32x4_t* p = (const u32x4_t*)((const bf16_t*)x + (size_t)my_row * d + j0);
+        if (x_loader) {
+            if (IS_BF16) {
+                const u32x4_t* p = (const u32x4_t*)((const bf16_t*)x + (size_t)my_row * d + j0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) xr[i] = p[i];
+                for (int i = 0; i < 4; ++i) xr[i] = p[i];
+            } else {
+                const u32x4_t* p = (const u32x4_t*)((const float*)x + (size_t)my_row * d + j0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) xr[i] = p[i];
+            }
         } else {
-            const u32x4_t* p = (const u32x4_t*)((const float*)x + (size_t)my_row * d + j0);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) xr[i] = p[i];
-        }
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int i = tid + 256 * r, jj = i >> 6, e = i & 63;
-            wr[r] = (e < E) ? w_router[(size_t)(j0 + jj) * E + e] : 0.0f;
+            for (int r = 0; r < 8; ++r) {
+                const int i = (tid - 256) + 256 * r, jj = i >> 6, e = i & 63;
+                wr[r] = (e < E) ? w_router[(size_t)(j0 + jj) * E + e] : 0.0f;
+            }
         }
     };
     auto store_stage = [&]() {
-        if (IS_BF16) {
+        if (x_loader) {
+            if (IS_BF16) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    xs[wave][8 * i + 2 * c][lane] = __uint_as_float(xr[i][c] << 16);
-                    xs[wave][8 * i + 2 * c + 1][lane] = __uint_as_float(xr[i][c] & 0xFFFF0000u);
-                }
+                    for (int c = 0; c < 4; ++c) {
+                        xs[wave][8 * i + 2 * c][lane] = __uint_as_float(xr[i][c] << 16);
+                        xs[wave][8 * i + 2 * c + 1][lane] = __uint_as_float(xr[i][c] & 0xFFFF0000u);
+                    }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) xs[wave][4 * i + c][lane] = __uint_as_float(xr[i][c]);
+            }
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) xs[wave][4 * i + c][lane] = __uint_as_float(xr[i][c]);
-        }
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int i = tid + 256 * r;
-            wsm[i >> 6][i & 63] = wr[r];
+            for (int r = 0; r < 8; ++r) {
+                const int i = (tid - 256) + 256 * r;
+                wsm[i >> 6][i & 63] = wr[r];
+            }
         }
     };
 
-    float acc[8][8];
+    float acc[8][4];
 #pragma unroll
     for (int a = 0; a < 8; ++a)
 #pragma unroll
-        for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0f;
 
     load_stage(0);
     for (int st = 0; st < NSTAGE; ++st) {
@@ -89,28 +99,25 @@ router_partial_kernel(const void* __restrict__ x, const float* __restrict__ w_ro
         if (st + 1 < NSTAGE) load_stage(st + 1);
 #pragma unroll 4
         for (int jj = 0; jj < SJ; ++jj) {
-            const f32x4_t x0 = *(const f32x4_t*)&xs[wave][jj][8 * tg];
-            const f32x4_t x1 = *(const f32x4_t*)&xs[wave][jj][8 * tg + 4];
-            const f32x4_t w0 = *(const f32x4_t*)&wsm[jj][8 * eg];
-            const f32x4_t w1 = *(const f32x4_t*)&wsm[jj][8 * eg + 4];
+            const f32x4_t x0 = *(const f32x4_t*)&xs[tw][jj][8 * tg];
+            const f32x4_t x1 = *(const f32x4_t*)&xs[tw][jj][8 * tg + 4];
+            const f32x4_t w0 = *(const f32x4_t*)&wsm[jj][32 * eh + 4 * eg];
 #pragma unroll
             for (int a = 0; a < 8; ++a) {
                 const float xv = a < 4 ? x0[a & 3] : x1[a & 3];
 #pragma unroll
-                for (int b = 0; b < 8; ++b) acc[a][b] = __builtin_fmaf(xv, b < 4 ? w0[b & 3] : w1[b & 3], acc[a][b]);
+                for (int b = 0; b < 4; ++b) acc[a][b] = __builtin_fmaf(xv, w0[b], acc[a][b]);
             }
         }
     }
 
 #pragma unroll
     for (int a = 0; a < 8; ++a) {
-        const int t = tok_base + wave * 64 + 8 * tg + a;
+        const int t = tok_base + tw * 64 + 8 * tg + a;
         if (t < T) {
-            float* o = partial + ((size_t)seg * T + t) * 64 + 8 * eg;
+            float* o = partial + ((size_t)seg * T + t) * 64 + 32 * eh + 4 * eg;
             f32x4_t v0 = {acc[a][0], acc[a][1], acc[a][2], acc[a][3]};
-            f32x4_t v1 = {acc[a][4], acc[a][5], acc[a][6], acc[a][7]};
             *(f32x4_t*)o = v0;
-            *(f32x4_t*)(o + 4) = v1;
         }
     }
 }
@@ -513,7 +520,7 @@ static hipError_t launch_partials(const RoutingArgs& a, hipStream_t s) {
         hipLaunchKernelGGL((router_partial_small_kernel<IS_BF16, TW>), dim3(nseg, (a.T + TW - 1) / TW), dim3(64), 0, s,
                            a.x, a.w_router, a.T, a.d, a.E, a.partial);
     } else {
-        hipLaunchKernelGGL((router_partial_kernel<IS_BF16>), dim3((a.T + 255) / 256, nseg), dim3(256), 0, s, a.x,
+        hipLaunchKernelGGL((router_partial_kernel<IS_BF16>), dim3((a.T + 255) / 256, nseg), dim3(512), 0, s, a.x,
                            a.w_router, a.T, a.d, a.E, a.partial);
     }
     return hipGetLastError();
