@@ -42,7 +42,8 @@
  *     accumulation is fp32.  dtype LEXI_F32: everything fp32.
  *   - Shape limits: 1 <= E <= 64, d % 128 == 0, F % 64 == 0, F_shared % 64 == 0,
  *     1 <= k <= E, T >= 0 (T == 0 returns LEXI_OK and launches nothing),
- *     T * k < 2^24.  Every device pointer must be 16-byte aligned.
+ *     T * k < 2^24; x, the SwiGLU intermediate of the routed experts (T*k rows of F) and of the shared expert
+ *     (T rows of F_shared) each stay below 4 GiB.  Every device pointer must be 16-byte aligned.
  *   - Routing semantics: selection on the fp32 logits in the total order (logit
  *     descending, expert index ascending) -- ties go to the lower index, +0 == -0;
  *     inputs must be finite.  The k selected experts are kept in rank order

@@ -126,6 +126,12 @@ lexi_status check_call(const lexi_layer_t* ly, const void* x, const void* y, int
     if (T < 0) return LEXI_ERR_SHAPE;
     if (k < 1 || k > ly->E) return LEXI_ERR_BAD_K;
     if ((int64_t)T * k >= (1 << 24)) return LEXI_ERR_SHAPE;
+    {   // the tile kernels address their input rows with 32-bit byte offsets
+        const uint64_t es = ly->dtype == LEXI_BF16 ? 2 : 4, lim = (uint64_t)1 << 32;
+        if ((uint64_t)T * ly->d * es >= lim || (uint64_t)T * k * ly->F * es >= lim ||
+            (uint64_t)T * ly->F_shared * es >= lim)
+            return LEXI_ERR_SHAPE;
+    }
     if (T == 0) return LEXI_OK;
     if (!x || !y || !workspace) return LEXI_ERR_NULL;
     if (misaligned(x) || misaligned(y) || misaligned(workspace)) return LEXI_ERR_ALIGN;
@@ -158,7 +164,7 @@ lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t
     const bool stream_routed = (int64_t)T * k <= (int64_t)kStreamRowsPerExpert * ly.E;
     FfnArgs g{};
     g.streaming = stream_routed;
-    g.is_bf16 = bf; g.in = x; g.row_token = w.row_token; g.w0 = ly.w_gate; g.w1 = ly.w_up; g.K = ly.d;
+    g.is_bf16 = bf; g.in = x; g.row_token = w.row_token; g.in_rows = T; g.w0 = ly.w_gate; g.w1 = ly.w_up; g.K = ly.d;
     g.features = ly.F; g.M = T * k; g.max_tiles = w.max_tiles; g.tile_tokens = kTileTokens; g.sched = w.sched;
     g.sched_count = w.sched_count; g.out = w.act;
     if (launch_gateup(g, s) != hipSuccess) return LEXI_ERR_LAUNCH;

@@ -40,15 +40,17 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_f0 = cb * (GATEUP ? 128 : 256) + wave * (GATEUP ? 32 : 64);  // first output feature
     const bool active = wave_f0 < features;
     const int l16 = lane & 15, kq = lane >> 4;
     const int koff = kq * 8;
 
-    // ---- weight fragment pointers: feature block fb of this wave is 16 packed rows; one K-step of 32 is one 1 KB
-    //      block, lane reads its 16 bytes at lane*8 elements; successive K-steps are 512 elements apart.
-    const bf16_t* aptr[WB];
+    // ---- weight fragments: feature block fb of this wave is 16 packed rows; one K-step of 32 is one 1 KB block, a
+    //      lane reads its 16 bytes at lane*16; successive K-steps are 1 KB apart.  The block-row origins are
+    //      wave-uniform and live in scalar registers, the lane part is one 32-bit offset (a packed 16-row slab is
+    //      32*K bytes, far below 4 GiB): 64-bit per-lane pointers would push the kernel over its 256 registers.
+    const char* abase[WB];
 #pragma unroll
     for (int fb = 0; fb < WB; ++fb) {
         int row;
@@ -60,23 +62,24 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
             row = wave_f0 + 16 * fb;
         }
         row = active ? row : 0;
-        aptr[fb] = base + ((size_t)ti.expert * (features >> 4) + (row >> 4)) * ((size_t)K * 16) + lane * 8;
+        abase[fb] = (const char*)(base + ((size_t)ti.expert * (features >> 4) + (row >> 4)) * ((size_t)K * 16));
     }
+    const uint32_t alane = lane * 16;
 
     // ---- token tile staging: thread owns 16-byte chunk (tid % 8) of rows tid/8 + 32p ----
     const int chunk = tid & 7;
-    const bf16_t* xsrc[4];
+    uint32_t xoff[4];   // byte offsets from `in` (the launcher rejects inputs of 4 GiB or more)
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int r = (tid >> 3) + 32 * p;
         const int rr = min(r, ti.rows - 1);  // rows past the group end re-read its last row; never stored
         const int src_row = row_token ? row_token[ti.row0 + rr] : ti.row0 + rr;
-        xsrc[p] = in + (size_t)src_row * K + chunk * 8;
+        xoff[p] = (uint32_t)(((size_t)src_row * K + chunk * 8) * 2);
     }
     u32x4_t xreg[4];
     auto load_x = [&](int kt) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) xreg[p] = *(const u32x4_t*)(xsrc[p] + kt * BK);
+        for (int p = 0; p < 4; ++p) xreg[p] = *(const u32x4_t*)((const char*)in + (xoff[p] + (uint32_t)kt * (BK * 2)));
     };
     auto store_x = [&](int buf) {
 #pragma unroll
@@ -98,7 +101,7 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
 #pragma unroll
     for (int fb = 0; fb < WB; ++fb)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) areg[fb][ks] = *(const bf16x8_t*)(aptr[fb] + ks * 512);
+        for (int ks = 0; ks < KS; ++ks) areg[fb][ks] = *(const bf16x8_t*)(abase[fb] + (alane + (uint32_t)ks * 1024u));
     store_x(0);
     __syncthreads();
 
@@ -124,7 +127,7 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
                     for (int tb = 0; tb < NTB; ++tb)
                         acc[fb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[fb][ks], b[tb], acc[fb][tb], 0, 0, 0);
 #pragma unroll
-                for (int fb = 0; fb < WB; ++fb) areg[fb][ks] = *(const bf16x8_t*)(aptr[fb] + (size_t)(kn * KS + ks) * 512);
+                for (int fb = 0; fb < WB; ++fb) areg[fb][ks] = *(const bf16x8_t*)(abase[fb] + (alane + (uint32_t)(kn * KS + ks) * 1024u));
                 __builtin_amdgcn_sched_barrier(0);  // refill each fragment right after its last use, one k-step at a time
             }
             store_x(buf ^ 1);
@@ -251,6 +254,9 @@ static hipError_t launch_ffn(const FfnArgs& a, hipStream_t s) {
     if (a.max_tiles <= 0) return hipSuccess;
     if (a.is_bf16 && a.streaming) return GATEUP ? launch_gateup_stream(a, s) : launch_down_stream(a, s);
     if (a.is_bf16) {
+        // the tile kernel addresses its input rows with 32-bit byte offsets
+        const size_t in_rows = a.row_token ? (size_t)a.in_rows : (size_t)a.M;
+        if (in_rows * (size_t)a.K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
         const int ncb = (a.features + (GATEUP ? 127 : 255)) / (GATEUP ? 128 : 256);
         const dim3 grid(xcd_grid(ncb, a.max_tiles));
         hipLaunchKernelGGL((ffn_mfma_kernel<GATEUP>), grid, dim3(256), 0, s, (const bf16_t*)a.in, a.row_token,

@@ -38,6 +38,7 @@ struct FfnArgs {
     bool streaming;            // few rows per expert: use the weight-streaming (HBM-bound) schedule
     const void* in;            // row-major [*][K]
     const int32_t* row_token;  // gather map row -> input row, or null (identity)
+    int in_rows;               // rows of `in` when row_token is given (bound of the gather)
     const void* w0;            // gate (GATE/UP) or down weights, [E] packed matrices of [features][K]
     const void* w1;            // up weights or null
     int K;                     // reduction length
