@@ -160,6 +160,66 @@ def pruning_sweep(args, cfg0, T):
                       "config": {"workload": f"{cfg0.name} L={args.layers or cfg0.L} d={cfg0.d} T={T}"}, "rows": rows}), flush=True)
 
 
+def budget_sweep(args, cfg, T):
+    """tokens/s of the stack for seeded per-layer k vectors at the budgets B = L * kbar, kbar = k_min .. k_base (the
+    last one is the uniform baseline), the way the paper's figures quote a model at several budgets.  One JSON line."""
+    from dataclasses import replace
+
+    import numpy as np
+    import torch
+
+    import lexi_synth as S
+    import paper_2509_02753_amd as P
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    L = cfg.L
+    layers = []
+    for l in range(L):
+        rm = S.device_layer(cfg, l, dev)
+        layers.append(P.Layer.from_tensors(rm, shared_kind=cfg.shared_kind))
+        del rm
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    x = torch.empty((L, T, cfg.d), dtype=tdt, device=dev)
+    for l in range(L):
+        S.fill_device(x[l], cfg.seed, S.tensor_id(l, S.KIND_X), cfg.sigma_x)
+    y = torch.empty((L, T, cfg.d), dtype=torch.float32, device=dev)
+    ws = P.alloc_workspace(layers, T, int(cfg.k_base))
+    arr = P.binding._layer_array(layers)
+    prefill = (T * float(cfg.k_base) / cfg.E) >= 64
+    use_graph = args.graph == "on" or (args.graph == "auto" and not prefill)
+    rows = []
+    budgets = sorted({L * kb for kb in range(cfg.k_min, cfg.k_base + 1)} | {cfg.budget})
+    for B in budgets:
+        kv = cfg.k_uniform() if B == L * cfg.k_base else replace(cfg, budget=B, fixed_kvec=None).k_lexi()
+        assert int(kv.sum()) == B
+        call = lambda: P.lexi_moe_stack_forward(layers, kv, x, y, ws, layer_array=arr)
+        call()
+        torch.cuda.synchronize()
+        step = call
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                call()
+            step = g.replay
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / args.steps
+        rows.append({"budget": int(B), "k_vec": kv.tolist(), "ms_per_step": round(sec * 1e3, 4), "tokens_per_s": round(T / sec, 1)})
+        log(f"[sweep] B={B}: {sec * 1e3:.3f} ms/step, {T / sec:,.0f} tokens/s")
+    base = rows[-1]["tokens_per_s"]
+    for r in rows:
+        r["vs_uniform_k"] = round(r["tokens_per_s"] / base, 4)
+    print(json.dumps({"metric": "MoE-stack tokens/s", "sweep": "budgets", "unit": "tokens/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                      "config": {"workload": f"{cfg.name} L={L} d={cfg.d} E={cfg.E} F={cfg.F} Fs={cfg.F_shared} T={T}",
+                                 "hip_graph": bool(use_graph)}, "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -177,8 +237,9 @@ def main():
     ap.add_argument("--no-ceilings", action="store_true", help="skip the matrix-core / HBM ceiling probes")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="end with one 256 MiB device-to-device copy kernel (counter runs scale FETCH_SIZE / WRITE_SIZE by it)")
-    ap.add_argument("--sweep", default=None, choices=["pruning"],
-                    help="instead of the benchmark line: tokens/s vs active experts for the baseline and the pruned shapes")
+    ap.add_argument("--sweep", default=None, choices=["pruning", "budgets"],
+                    help="instead of the benchmark line: tokens/s vs active experts for the baseline and the pruned shapes "
+                         "(pruning), or tokens/s of per-layer k vectors at every budget B = L*k, k = k_min..k_base (budgets)")
     ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
                     help="replay the stack call from a captured HIP graph (auto: for decode-sized batches, whose steps are launch-bound)")
     args = ap.parse_args()
@@ -196,6 +257,8 @@ def main():
     T = args.T if args.T is not None else cfg.T_regimes[0]
     if args.sweep == "pruning":
         return pruning_sweep(args, cfg, T)
+    if args.sweep == "budgets":
+        return budget_sweep(args, cfg, T)
     L = args.layers if args.layers else cfg.L
     kvec = (cfg.k_lexi() if args.kvec == "lexi" else cfg.k_uniform())[:L]
     kuni = cfg.k_uniform()[:L]

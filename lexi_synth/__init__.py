@@ -14,7 +14,7 @@ from typing import Dict, Optional
 import numpy as np
 
 from . import generator
-from .configs import (C1, C2, C3, C4, C5, CONFIGS, SHARED_NONE, SHARED_SIGMOID, SHARED_UNGATED, MoEConfig, mini, pruned)
+from .configs import (C1, C2, C3, C4, C5, C6, C7, CONFIGS, SHARED_NONE, SHARED_SIGMOID, SHARED_UNGATED, MoEConfig, mini, pruned)
 from .generator import (KIND_W_DOWN, KIND_W_GATE, KIND_W_ROUTER, KIND_W_SHARED_GATE, KIND_W_UP, KIND_WS_DOWN,
                         KIND_WS_GATE, KIND_WS_UP, KIND_X, tensor_id, zipf_router_bias)
 

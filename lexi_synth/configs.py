@@ -1,4 +1,4 @@
-"""The five synthetic MoE-stack workloads and their scaled-down test shapes.
+"""The synthetic MoE-stack workloads and their scaled-down test shapes.
 
 Shapes follow the paper's Table 1 (layers, experts, baseline top-k, FFN dim)
 for OLMoE-1B-7B, Qwen1.5-MoE-A2.7B, Mixtral-8x7B and DeepSeek-V2-Lite; hidden
@@ -72,7 +72,15 @@ C4 = MoEConfig("c4_mixtral", 4, L=32, d=4096, E=8, F=14336, dtype="bf16", k_base
 C5 = MoEConfig("c5_dsv2lite", 5, L=26, d=2048, E=64, F=1408, dtype="bf16", k_base=6, k_min=2, k_max=6,
                budget=104, T_regimes=(1, 16, 64, 256), F_shared=2816, shared_kind=SHARED_UNGATED, zipf_s=1.1)
 
-CONFIGS = {c.name: c for c in (C1, C2, C3, C4, C5)}
+# The two remaining rows of the paper's Table 1, as shape variants for the throughput sweeps (hidden sizes and the
+# shared experts of the DeepSeek-VL2 language model from the public model cards; 11 of its 12 layers are MoE layers,
+# which is what the budgets 44 and 55 of the paper's figures are multiples of).
+C6 = MoEConfig("c6_minicpm", 6, L=40, d=2304, E=8, F=5760, dtype="bf16", k_base=2, k_min=1, k_max=2,
+               budget=60, T_regimes=(4096,))
+C7 = MoEConfig("c7_vl2tiny", 7, L=11, d=1280, E=64, F=896, dtype="bf16", k_base=6, k_min=2, k_max=6,
+               budget=44, T_regimes=(4096,), F_shared=1792, shared_kind=SHARED_UNGATED)
+
+CONFIGS = {c.name: c for c in (C1, C2, C3, C4, C5, C6, C7)}
 
 
 def mini(cfg: MoEConfig, L: int = 2, d: int = 256, F: int = 384, F_shared: Optional[int] = None) -> MoEConfig:

@@ -44,6 +44,13 @@ def test_pruned_shapes(name, inter, intra, T, k):
     run_and_check_layer(cfg, 0, T, k)
 
 
+@pytest.mark.parametrize("name,T,k", [("c6_minicpm", 160, 2), ("c6_minicpm", 20, 1), ("c7_vl2tiny", 300, 6), ("c7_vl2tiny", 9, 3)])
+def test_remaining_table1_shapes_one_full_layer(name, T, k):
+    """The two Table 1 shapes that are not benchmark workloads, at their real widths (hidden sizes that are not powers
+    of two: 18 and 10 router segments, 9 and 5 down-GEMM column blocks), one layer, every token compared."""
+    run_and_check_layer(S.CONFIGS[name], 0, T, k)
+
+
 def test_repeated_calls_and_k_changes_leave_no_state():
     """UpdateTopk changes k only: k=2, then k=8, then k=2 again reproduces the first result bit for bit."""
     import torch
