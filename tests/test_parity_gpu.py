@@ -166,3 +166,37 @@ def test_stack_replayed_from_a_hip_graph_matches_eager():
         P.lexi_moe_stack_forward(dls, kv, x, y_other, ws)     # eager work between the replays
         torch.cuda.synchronize()
         assert torch.equal(y_other, y_eager)
+
+
+def _random_shape_cases(n, seed):
+    """Seeded shapes inside the documented limits: d a multiple of 128, F and F_shared multiples of 64, 1 <= E <= 64,
+    1 <= k <= E, any T; every routing path (T <= 16, <= 128, <= 1024, above) and every shared-expert kind appears."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    t_pool = [1, 2, 3, 7, 15, 16, 17, 31, 33, 64, 100, 127, 128, 129, 200, 257, 511, 700, 1023, 1024, 1025, 1500, 2049]
+    for i in range(n):
+        E = int(rng.choice([1, 2, 3, 5, 8, 13, 31, 32, 33, 48, 60, 63, 64]))
+        d = 128 * int(rng.integers(1, 7))
+        F = 64 * int(rng.integers(1, 9))
+        kind = int(rng.integers(0, 3))
+        Fs = 64 * int(rng.integers(1, 7)) if kind else 0
+        T = int(t_pool[i % len(t_pool)])
+        k = int(rng.integers(1, E + 1)) if i % 3 else min(E, int(rng.choice([1, 2, E])))
+        zipf = 1.1 if rng.random() < 0.3 else 0.0
+        dtype = "f32" if i % 7 == 6 else "bf16"
+        cases.append((i, E, d, F, Fs, kind, T, k, zipf, dtype))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_shape_cases(46, 20250902), ids=lambda c: f"{c[0]}-E{c[1]}d{c[2]}F{c[3]}s{c[4]}T{c[6]}k{c[7]}{c[9]}")
+def test_random_shapes_inside_the_limits(case):
+    """Every token of one layer against the oracle on seeded random shapes: ragged column blocks (F, d not multiples
+    of the 128/256-wide workgroup tiles), expert counts that are not powers of two, k anywhere in 1..E, empty experts
+    under a Zipf bias, fp32 and bf16 layers, all three shared-expert kinds."""
+    from dataclasses import replace
+    i, E, d, F, Fs, kind, T, k, zipf, dtype = case
+    cfg = replace(S.C2, name=f"rand{i}", number=100 + i, L=1, d=d, E=E, F=F, dtype=dtype, k_base=k, k_min=1, k_max=E,
+                  budget=k, F_shared=Fs, shared_kind=kind, zipf_s=zipf, fixed_kvec=None)
+    if T * k * F * 3 * d > 3e10:      # keep the fp64 oracle of one case to a few seconds
+        T = max(1, int(3e10 / (k * F * 3 * d)))
+    run_and_check_layer(cfg, 0, T, k, check_bf16_out=(i % 4 == 0))
