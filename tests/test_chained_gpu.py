@@ -138,3 +138,34 @@ def test_chained_mode_rejects_what_it_cannot_run():
     with pytest.raises(RuntimeError):      # one input per layer
         P.lexi_moe_stack_forward(dls, kv, torch.stack([x, x]),
                                  torch.empty((cfg.L, T, cfg.d), dtype=torch.float32, device="cuda:0"), ws, chained=True)
+
+
+def test_chained_stack_replayed_from_a_hip_graph_matches_eager():
+    """The whole chain (normalisation, routing, expert GEMMs, shared expert on its side stream, combine + residual of
+    every block) captured once and replayed: every replay equals the eager result, with eager work in between."""
+    import torch
+    import paper_2509_02753_amd as P
+    cfg = S.mini(S.C5, L=4, d=256, F=384)
+    T = 12
+    kv = cfg.k_lexi()
+    dls = [device_and_host_layer(cfg, l)[0] for l in range(cfg.L)]
+    x = S.device_x(cfg, 0, T)
+    y_eager = torch.empty((T, cfg.d), dtype=torch.float32, device="cuda:0")
+    y_graph = torch.empty_like(y_eager)
+    ws = P.alloc_workspace(dls, T, int(kv.max()))
+    ws2 = P.alloc_workspace(dls, T, int(kv.max()))
+    P.lexi_moe_stack_forward(dls, kv, x, y_eager, ws, chained=True)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        P.lexi_moe_stack_forward(dls, kv, x, y_graph, ws2, chained=True)
+    for i in range(4):
+        y_graph.fill_(float("nan"))
+        ws2.fill_(0xFF)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), f"replay {i} differs from the eager result"
+        y_other = torch.empty_like(y_eager)
+        P.lexi_moe_stack_forward(dls, kv, x, y_other, ws, chained=True)
+        torch.cuda.synchronize()
+        assert torch.equal(y_other, y_eager)
