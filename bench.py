@@ -24,7 +24,8 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-FFN_SOURCES = ("ffn.hip", "ffn_common.hpp", "ffn_stream.hip", "common.hpp", "kernels.hpp")
+# the files that hold the code of the expert-FFN kernels (the launch-argument structs of all kernels are elsewhere)
+FFN_SOURCES = ("ffn.hip", "ffn_common.hpp", "ffn_stream.hip", "common.hpp")
 
 
 def ffn_source_digest():

@@ -74,6 +74,9 @@ Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
     const size_t nblk = ((size_t)T + 7) / 8;  // router blocks never hold fewer than 8 tokens
     // every expert with rows has one ragged tile at most, the rest are full
     w.max_tiles = (int)(A / kTileTokens) + (int)(A < (size_t)ly.E ? A : (size_t)ly.E);
+    // chained stack: the normalised MoE input.  First, so that its place does not depend on the layer or on k: a
+    // block's combine writes the next block's input there.
+    w.u = c.take<char>((size_t)T * ly.d * es);
     w.partial = c.take<float>((size_t)(ly.d / 128) * T * 64);
     w.topk_idx = c.take<int32_t>(A);
     w.gates = c.take<float>(A);
@@ -92,7 +95,6 @@ Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
         w.act_shared = c.take<char>((size_t)T * ly.F_shared * es);
         w.y_shared = c.take<float>((size_t)T * ly.d);
     }
-    w.u = c.take<char>((size_t)T * ly.d * es);   // chained stack: the normalised MoE input
     w.bytes = align_up(c.used, 256);
     return w;
 }
@@ -183,11 +185,13 @@ lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t
 }
 
 // One layer, arguments already validated.
-// `hidden` != null selects the chained block: x is ignored, the MoE input is the normalised hidden state and the
-// block's output is added to it (y may be `hidden` itself).
+// `hidden` != null selects the chained block: the MoE input is `u_in` (the normalised hidden state, written by the
+// caller or by the previous block's combine), the block's output is added to `hidden` (y may be `hidden` itself), and
+// with `u_out` the combine also writes the next block's normalised input.
 lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_dtype, int32_t T, int32_t k,
                       void* workspace, hipStream_t s, const lexi_routing_out_t* dbg,
-                      const lexi_stage_events_t* events = nullptr, const float* hidden = nullptr) {
+                      const lexi_stage_events_t* events = nullptr, const float* hidden = nullptr,
+                      const void* u_in = nullptr, void* u_out = nullptr) {
     auto mark = [&](int i) {
         if (events && events->ev[i]) (void)hipEventRecord((hipEvent_t)events->ev[i], s);
     };
@@ -195,9 +199,7 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     Workspace w = carve(ly, T, k, workspace);
     const bool bf = ly.dtype == LEXI_BF16;
     if (hidden != nullptr) {
-        void* u = (dbg && dbg->moe_input) ? dbg->moe_input : w.u;
-        if (launch_rmsnorm(hidden, T, ly.d, kRmsEps, u, bf, s) != hipSuccess) return LEXI_ERR_LAUNCH;
-        x = u;
+        x = u_in;
     } else if (dbg && dbg->moe_input) {
         if (hipMemcpyAsync(dbg->moe_input, x, (size_t)T * ly.d * (bf ? 2 : 4), hipMemcpyDeviceToDevice, s) != hipSuccess)
             return LEXI_ERR_LAUNCH;
@@ -258,7 +260,7 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     c.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr;
     c.x = x; c.x_bf16 = bf;
     c.w_shared_gate = ly.shared_kind == LEXI_SHARED_SIGMOID ? ly.w_shared_gate : nullptr;
-    c.residual = hidden;
+    c.residual = hidden; c.u_next = u_out;
     c.T = T; c.d = ly.d; c.k = k; c.y = y; c.y_bf16 = y_dtype == LEXI_BF16;
     if (launch_combine(c, s) != hipSuccess) return LEXI_ERR_LAUNCH;
     mark(5);
@@ -336,15 +338,22 @@ lexi_status lexi_moe_stack_forward_profiled(const lexi_layer_t* layers, int32_t 
     if (T == 0) return LEXI_OK;
     hipStream_t s = (hipStream_t)hip_stream;
     if (chained) {
-        // h_0 = x, widened into the first output buffer; block l reads h_l where block l-1 left it and writes h_{l+1}
+        // h_0 = x, widened into the first output buffer; block l reads h_l where block l-1 left it and writes h_{l+1}.
+        // The normalised input of block 0 comes from its own kernel, that of every later block from the combine of
+        // the block before it; it lives at the start of the workspace unless the caller asked to see it.
+        const bool bf = layers[0].dtype == LEXI_BF16;
+        auto u_of = [&](int l) -> void* {
+            return (dbg_per_layer && dbg_per_layer[l].moe_input) ? dbg_per_layer[l].moe_input : workspace;
+        };
         float* h = (float*)y;
-        if (launch_widen(x, layers[0].dtype == LEXI_BF16, (size_t)T * layers[0].d, h, s) != hipSuccess)
-            return LEXI_ERR_LAUNCH;
+        if (launch_widen(x, bf, (size_t)T * layers[0].d, h, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+        if (launch_rmsnorm(h, T, layers[0].d, kRmsEps, u_of(0), bf, s) != hipSuccess) return LEXI_ERR_LAUNCH;
         for (int l = 0; l < L; ++l) {
             float* h_out = (float*)y + (size_t)l * y_layer_stride;
             lexi_status st = run_layer(layers[l], nullptr, h_out, LEXI_F32, T, k_vec[l], workspace, s,
                                        dbg_per_layer ? &dbg_per_layer[l] : nullptr,
-                                       events_per_layer ? &events_per_layer[l] : nullptr, h);
+                                       events_per_layer ? &events_per_layer[l] : nullptr, h, u_of(l),
+                                       l + 1 < L ? u_of(l + 1) : nullptr);
             if (st != LEXI_OK) return st;
             h = h_out;
         }

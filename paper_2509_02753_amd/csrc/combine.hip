@@ -4,14 +4,34 @@
 
 namespace lexi {
 
+// u = h * inv rounded to the layer dtype, four consecutive elements (the chained stack's normalised MoE input).
+template <bool U_BF16>
+__device__ __forceinline__ void store_normalised(void* u, size_t idx, const f32x4_t& v, float inv) {
+    if (U_BF16) {
+        u32x2_t pk;
+        pk[0] = (uint32_t)f32_to_bf16(v[0] * inv) | ((uint32_t)f32_to_bf16(v[1] * inv) << 16);
+        pk[1] = (uint32_t)f32_to_bf16(v[2] * inv) | ((uint32_t)f32_to_bf16(v[3] * inv) << 16);
+        *(u32x2_t*)((bf16_t*)u + idx) = pk;
+    } else {
+        f32x4_t o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = v[i] * inv;
+        *(f32x4_t*)((float*)u + idx) = o;
+    }
+}
+
 // One workgroup per token; each thread owns 4 consecutive output features per pass.  For a sigmoid-gated shared
 // expert the workgroup first evaluates its token's gate coefficient 1 / (1 + exp(-(x[t] . w_sg))) itself (wave sums by
 // DPP, the four wave results added in wave order), which saves a launch.
+// Chained stack: `residual` (the hidden state) is added to the block's output, and with `u_next` the same workgroup
+// also writes the NEXT block's normalised input from the row it has just produced -- the sum of squares in exactly
+// the order rmsnorm_kernel uses, so either route gives the same bits.  (x and u_next may be the same buffer: a
+// workgroup reads its row of x before it writes its row of u_next.)
 template <bool Y_BF16, bool X_BF16>
 __global__ void __launch_bounds__(256)
 combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv_perm, const float* __restrict__ gates,
-               const float* __restrict__ y_shared, const void* __restrict__ x, const void* __restrict__ w_shared_gate,
-               const float* residual, int d, int k, void* y) {
+               const float* __restrict__ y_shared, const void* x, const void* __restrict__ w_shared_gate,
+               const float* residual, int d, int k, void* y, void* u_next, float eps) {
     __shared__ float wave_part[4];
     const int t = blockIdx.x;
     const int32_t* ip = inv_perm + (size_t)t * k;
@@ -27,6 +47,7 @@ combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv
         const float z = ((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3];
         coef = 1.0f / (1.0f + __expf(-z));
     }
+    float ss = 0.0f;
     for (int j = threadIdx.x * 4; j < d; j += 256 * 4) {
         f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int s = 0; s < k; ++s) {  // slot order = rank order
@@ -45,6 +66,8 @@ combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[i] = h[i] + acc[i];
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ss = __builtin_fmaf(acc[i], acc[i], ss);
         if (Y_BF16) {
             u32x2_t pk;
             pk[0] = pack_bf16x2(acc[0], acc[1]);
@@ -54,12 +77,23 @@ combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv
             *(f32x4_t*)((float*)y + (size_t)t * d + j) = acc;
         }
     }
+    if (Y_BF16 || u_next == nullptr) return;   // (the chained stack keeps its hidden state in fp32)
+    __syncthreads();                            // wave_part may still be read for the gate coefficient
+    const float ws = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = ws;
+    __syncthreads();
+    const float total = ((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3];
+    const float inv = 1.0f / sqrtf(total / (float)d + eps);
+    for (int j = threadIdx.x * 4; j < d; j += 256 * 4) {
+        const f32x4_t v = *(const f32x4_t*)((const float*)y + (size_t)t * d + j);   // this thread's own stores
+        store_normalised<X_BF16>(u_next, (size_t)t * d + j, v, inv);
+    }
 }
 
 template <bool Y_BF16, bool X_BF16>
 static void launch_combine_t(const CombineArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((combine_kernel<Y_BF16, X_BF16>), dim3(a.T), dim3(256), 0, s, a.y_slot, a.inv_perm, a.gates,
-                       a.y_shared, a.x, a.w_shared_gate, a.residual, a.d, a.k, a.y);
+                       a.y_shared, a.x, a.w_shared_gate, a.residual, a.d, a.k, a.y, a.u_next, kRmsEps);
 }
 
 // Chained stack: u[t] = h[t] / sqrt(mean_j h[t][j]^2 + eps), rounded to the layer dtype.  One workgroup per token;
@@ -84,17 +118,7 @@ rmsnorm_kernel(const float* __restrict__ h, int d, float eps, void* __restrict__
     const float inv = 1.0f / sqrtf(total / (float)d + eps);
     for (int j = threadIdx.x * 4; j < d; j += 1024) {
         const f32x4_t v = *(const f32x4_t*)(ht + j);   // second read of the row: served by the cache
-        if (U_BF16) {
-            u32x2_t pk;
-            pk[0] = (uint32_t)f32_to_bf16(v[0] * inv) | ((uint32_t)f32_to_bf16(v[1] * inv) << 16);
-            pk[1] = (uint32_t)f32_to_bf16(v[2] * inv) | ((uint32_t)f32_to_bf16(v[3] * inv) << 16);
-            *(u32x2_t*)((bf16_t*)u + (size_t)t * d + j) = pk;
-        } else {
-            f32x4_t o;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = v[i] * inv;
-            *(f32x4_t*)((float*)u + (size_t)t * d + j) = o;
-        }
+        store_normalised<U_BF16>(u, (size_t)t * d + j, v, inv);
     }
 }
 

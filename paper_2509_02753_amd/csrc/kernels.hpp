@@ -69,6 +69,7 @@ struct CombineArgs {
     const float* residual;     // [T][d] fp32 added to the result (chained stack), or null; may alias y
     void* y;                   // [T][d]
     bool y_bf16;
+    void* u_next;              // chained stack: [T][d] layer dtype, the next block's normalised input, or null
 };
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
 
