@@ -367,6 +367,20 @@ def main():
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
                     "traffic": stored_traffic(cfg.name, T), "avg_launch_ms": round(gu_ms_avg, 4),
                     "bytes_per_launch": gu_bytes / L}
+    # the same launch per distinct k: a layer with few active experts has fewer FLOPs per weight byte, so its binding
+    # roofline (the larger of FLOPs / MFMA peak and bytes / HBM peak) can be the other one
+    es = 4 if cfg.dtype == "f32" else 2
+    per_k = []
+    for kk in sorted(set(int(v) for v in kvec)):
+        ls = [l for l in range(L) if int(kvec[l]) == kk]
+        ms = float(np.mean([stage_ms[l, 1] for l in ls]))
+        fl = 4.0 * T * kk * cfg.d * cfg.F
+        by = float(np.mean([int((counts[l] > 0).sum()) for l in ls])) * 2 * cfg.d * cfg.F * es + T * cfg.d * es
+        t_mfma, t_hbm = fl / (PEAK_BF16_TFLOPS * 1e12), by / (PEAK_HBM_GBS * 1e9)
+        per_k.append({"k": kk, "layers": len(ls), "avg_launch_ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 1),
+                      "gbs": round(by / ms / 1e6, 1), "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                      "frac": round(max(t_mfma, t_hbm) / (ms * 1e-3), 4)})
+    roofline["per_k"] = per_k
     whole = {"flops_per_step": tot_flops, "bytes_per_step": tot_bytes,
              "mfma_frac": round(tot_flops / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
              "hbm_frac": round(tot_bytes / sec / 1e9 / PEAK_HBM_GBS, 4)}
