@@ -1,5 +1,5 @@
 // LExI Stage 2 (paper Algorithm 2): evolutionary allocation of the per-layer top-k under a total budget, guided by
-// the Stage-1 losses.  Host code only ("without needing to load the actual model", Sec. 4): nothing here touches the GPU.
+// the Stage-1 losses.  Host code only (the search runs on the loss table alone and needs no model weights, Sec. 4): nothing here touches the GPU.
 //
 // The paper leaves several steps open; the reading implemented here:
 //   population   n_pop feasible vectors: the flattest vector with sum B, then 4*L random balanced +-1 moves each
