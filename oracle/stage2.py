@@ -1,7 +1,7 @@
 """Oracle for LExI Stage 2 (paper Algorithm 2): evolutionary allocation of the per-layer top-k under a budget.
 
 Test infrastructure only (see the package header).  Plain Python, the algorithm's steps in the paper's order and
-notation.  The paper leaves several steps open; the reading taken here (and documented in the design doc) is:
+notation.  The paper leaves several steps open; the reading taken here is:
 
   population   N_pop feasible vectors: the flattest vector with sum B, then 4*L random balanced +-1 moves each
   fitness      phi(k) = sum_j D[j][k_j]                                   (lower is better)

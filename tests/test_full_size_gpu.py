@@ -39,13 +39,8 @@ def _sample_tokens(routing, T, k, E, seed):
 
 
 def _progress(msg):
-    """Progress lines for long runs: printed (visible with -s) and appended to gpurun_out/ when that folder exists."""
-    import os
+    """Progress lines for long runs (visible with -s)."""
     print(msg, flush=True)
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "test_full_size_progress.log"), "a") as f:
-            f.write(msg + "\n")
 
 
 def _check_workload(cfg, Ts, ffn_layers=None):
