@@ -245,7 +245,7 @@ def main():
                     help="replay the stack call from a captured HIP graph (auto: for decode-sized batches, whose steps are launch-bound)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
 
     import numpy as np
     import torch
