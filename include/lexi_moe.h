@@ -116,7 +116,8 @@ typedef enum { LEXI_STACK_INDEPENDENT = 0, LEXI_STACK_CHAINED = 1 } lexi_stack_m
 lexi_status lexi_pack_weights(const void* src, void* dst, int64_t n_matrices, int32_t rows, int32_t K, int32_t dtype,
                               void* hip_stream);
 
-/* Bytes of device workspace that any call with these layers, T <= T_max and k <= k_max needs.
+/* Bytes of device workspace that any call with these layers, T <= T_max and k <= k_max needs (per layer k is
+ * at most the layer's E, so k_max may exceed the E of some layers of a stack).
  * layers: host array[L].  Returns 0 if an argument is invalid. */
 size_t lexi_moe_workspace_bytes(const lexi_layer_t* layers, int32_t L, int32_t T_max, int32_t k_max);
 

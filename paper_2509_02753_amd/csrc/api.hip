@@ -291,8 +291,9 @@ size_t lexi_moe_workspace_bytes(const lexi_layer_t* layers, int32_t L, int32_t T
     if (!layers || L < 1 || T_max < 0 || k_max < 1) return 0;
     size_t need = 256;
     for (int l = 0; l < L; ++l) {
-        if (check_layer(&layers[l]) != LEXI_OK || k_max > layers[l].E) return 0;
-        const size_t b = carve(layers[l], T_max, k_max, nullptr).bytes;
+        if (check_layer(&layers[l]) != LEXI_OK) return 0;
+        // a layer cannot be asked for more active experts than it has
+        const size_t b = carve(layers[l], T_max, k_max < layers[l].E ? k_max : layers[l].E, nullptr).bytes;
         need = b > need ? b : need;
     }
     return need;

@@ -69,7 +69,7 @@ def test_workspace_query_is_monotone_and_checked():
                                                        ws_up=0x90000, ws_down=0xA0000))
     q = lambda T, k: int(_lib.lexi_moe_workspace_bytes(arr, 2, T, k))
     assert q(64, 2) > 0 and q(128, 2) > q(64, 2) and q(64, 4) > q(64, 2)
-    assert q(64, 9) == 0 and q(-1, 2) == 0 and q(64, 0) == 0
+    assert q(64, 9) == q(64, 8) and q(-1, 2) == 0 and q(64, 0) == 0     # k is capped by the layer's E (8 here)
     assert int(_lib.lexi_moe_workspace_bytes(None, 1, 64, 2)) == 0
     # a stack call validates every layer before launching: bad k in the second layer is reported, nothing runs
     kv = (ctypes.c_int32 * 2)(2, 0)

@@ -200,3 +200,34 @@ def test_random_shapes_inside_the_limits(case):
     if T * k * F * 3 * d > 3e10:      # keep the fp64 oracle of one case to a few seconds
         T = max(1, int(3e10 / (k * F * 3 * d)))
     run_and_check_layer(cfg, 0, T, k, check_bf16_out=(i % 4 == 0))
+
+
+def test_stack_of_layers_with_different_shapes():
+    """One stack call over layers that share only the hidden size: different expert counts, FFN widths, shared-expert
+    kinds and k; each layer must equal its own single-layer oracle result, and the workspace is sized for the largest."""
+    import torch
+    import paper_2509_02753_amd as P
+    from dataclasses import replace
+    T, d = 190, 384
+    shapes = [dict(E=64, F=448, F_shared=0, shared_kind=0, k=7, zipf_s=0.0),
+              dict(E=9, F=64, F_shared=320, shared_kind=2, k=9, zipf_s=0.0),
+              dict(E=33, F=704, F_shared=128, shared_kind=1, k=1, zipf_s=1.1),
+              dict(E=1, F=192, F_shared=0, shared_kind=0, k=1, zipf_s=0.0)]
+    cfgs = [replace(S.C2, name=f"het{i}", number=200 + i, L=len(shapes), d=d, E=s["E"], F=s["F"], F_shared=s["F_shared"],
+                    shared_kind=s["shared_kind"], zipf_s=s["zipf_s"], k_base=s["k"], k_min=1, k_max=s["E"], budget=s["k"],
+                    fixed_kvec=None) for i, s in enumerate(shapes)]
+    kv = np.array([s["k"] for s in shapes], dtype=np.int32)
+    pairs = [device_and_host_layer(cfgs[i], i) for i in range(len(shapes))]
+    dls = [p[0] for p in pairs]
+    x = torch.stack([S.device_x(cfgs[i], i, T) for i in range(len(shapes))])
+    y = torch.empty((len(shapes), T, d), dtype=torch.float32, device="cuda:0")
+    ws = P.alloc_workspace(dls, T, int(kv.max()))
+    assert ws.numel() >= max(P.lexi_moe_workspace_bytes([dl], T, int(k)) for dl, k in zip(dls, kv))
+    routs = [P.RoutingOut(T, int(kv[i]), shapes[i]["E"]) for i in range(len(shapes))]
+    ws.fill_(0x7F)
+    P.lexi_moe_stack_forward(dls, kv, x, y, ws, routing=routs)
+    torch.cuda.synchronize()
+    for i in range(len(shapes)):
+        ref = O.moe_layer(pairs[i][1], S.host_x(cfgs[i], i, T), int(kv[i]), round_act=True)
+        check_routing(routs[i], ref)
+        assert rel_err(y[i].cpu().numpy(), ref.out) <= TOL_BF16, f"layer {i}"
