@@ -169,3 +169,44 @@ def test_chained_stack_replayed_from_a_hip_graph_matches_eager():
         P.lexi_moe_stack_forward(dls, kv, x, y_other, ws, chained=True)
         torch.cuda.synchronize()
         assert torch.equal(y_other, y_eager)
+
+
+def test_chain_of_blocks_with_different_shapes():
+    """Blocks that share only the hidden size and dtype (different expert counts, widths, shared-expert kinds, k): the
+    normalised input handed from one block's combine to the next block must not depend on either block's layout."""
+    import torch
+    import paper_2509_02753_amd as P
+    T, d = 75, 256
+    shapes = [dict(E=64, F=320, F_shared=0, shared_kind=0, k=6, zipf_s=0.0),
+              dict(E=5, F=64, F_shared=192, shared_kind=2, k=5, zipf_s=0.0),
+              dict(E=40, F=576, F_shared=64, shared_kind=1, k=1, zipf_s=1.1)]
+    cfgs = [replace(S.C2, name=f"hetc{i}", number=300 + i, L=len(shapes), d=d, E=s["E"], F=s["F"], F_shared=s["F_shared"],
+                    shared_kind=s["shared_kind"], zipf_s=s["zipf_s"], k_base=s["k"], k_min=1, k_max=s["E"], budget=s["k"],
+                    fixed_kvec=None) for i, s in enumerate(shapes)]
+    kv = np.array([s["k"] for s in shapes], dtype=np.int32)
+    pairs = [device_and_host_layer(cfgs[i], i) for i in range(len(shapes))]
+    dls = [p[0] for p in pairs]
+    x = S.device_x(cfgs[0], 0, T)
+    ws = P.alloc_workspace(dls, T, int(kv.max()))
+    ws.fill_(0x7F)
+    y = torch.empty((len(shapes), T, d), dtype=torch.float32, device="cuda:0")
+    routs = [P.RoutingOut(T, int(kv[i]), shapes[i]["E"],
+                          moe_input=torch.empty((T, d), dtype=torch.bfloat16, device="cuda:0")) for i in range(len(shapes))]
+    P.lexi_moe_stack_forward(dls, kv, x, y, ws, routing=routs, chained=True)
+    torch.cuda.synchronize()
+    h_in = O.bf16_to_f64(to_numpy(x))
+    for i in range(len(shapes)):
+        u_gpu = to_numpy(routs[i].moe_input)
+        diff = np.abs(u_gpu.astype(np.int32) - O.bf16_rne(O.rms_norm(h_in)).astype(np.int32))
+        assert diff.max() <= 1 and np.mean(diff != 0) <= 0.01
+        h_ref, _, res = O.chained_layer(pairs[i][1], h_in, int(kv[i]), u_forced=u_gpu)
+        check_routing(routs[i], res)
+        h_out = y[i].cpu().numpy().astype(np.float64)
+        rms = float(np.sqrt(np.mean(res.out ** 2)))
+        assert (float(np.abs(h_out - h_ref).max()) - 2.0 ** -24 * float(np.abs(h_ref).max())) / rms <= TOL_BF16
+        h_in = h_out
+    # the same chain without the debugging outputs (normalised input in the workspace) and in place
+    y2 = torch.empty((T, d), dtype=torch.float32, device="cuda:0")
+    P.lexi_moe_stack_forward(dls, kv, x, y2, ws, chained=True)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y[-1])
