@@ -231,3 +231,43 @@ def test_stack_of_layers_with_different_shapes():
         ref = O.moe_layer(pairs[i][1], S.host_x(cfgs[i], i, T), int(kv[i]), round_act=True)
         check_routing(routs[i], ref)
         assert rel_err(y[i].cpu().numpy(), ref.out) <= TOL_BF16, f"layer {i}"
+
+
+def test_two_host_threads_on_two_streams():
+    """Two host threads drive the same layers on their own streams, workspaces and outputs (the shared expert's side
+    stream and its events are shared by all callers of a device): every result equals the single-threaded one."""
+    import threading
+    import torch
+    import paper_2509_02753_amd as P
+    cfg = S.mini(S.C3, L=3, d=256, F=384)    # sigmoid-gated shared expert -> side stream in every layer
+    T = 48
+    kv = cfg.k_lexi()
+    dls = [device_and_host_layer(cfg, l)[0] for l in range(cfg.L)]
+    x = torch.stack([S.device_x(cfg, l, T) for l in range(cfg.L)])
+    y_ref = torch.empty((cfg.L, T, cfg.d), dtype=torch.float32, device="cuda:0")
+    P.lexi_moe_stack_forward(dls, kv, x, y_ref, P.alloc_workspace(dls, T, int(kv.max())))
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(idx):
+        try:
+            stream = torch.cuda.Stream()
+            ws = P.alloc_workspace(dls, T, int(kv.max()))
+            ys = [torch.empty_like(y_ref) for _ in range(12)]
+            with torch.cuda.stream(stream):
+                for y in ys:
+                    P.lexi_moe_stack_forward(dls, kv, x, y, ws, stream=stream)
+            stream.synchronize()
+            for i, y in enumerate(ys):
+                if not torch.equal(y, y_ref):
+                    errors.append(f"thread {idx}, call {i}: result differs")
+        except Exception as e:  # noqa: BLE001  (reported through the list: exceptions do not cross threads)
+            errors.append(f"thread {idx}: {e!r}")
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads), "a worker did not finish"
+    assert not errors, errors
