@@ -60,6 +60,8 @@ def test_argument_validation_returns_codes_without_launching():
     assert call_layer(P, fake_layer(P, F_shared=128, shared_kind=2, ws_gate=0x80000, ws_up=0x90000,
                                     ws_down=0xA0000)) == -1                         # sigmoid gate vector missing
     assert call_layer(P, ok, T=1 << 23, k=2) == -2                                  # T*k >= 2^24
+    assert call_layer(P, fake_layer(P, F=65536), T=16384, k=2) == -2                # intermediate of 4 GiB or more
+    assert call_layer(P, fake_layer(P, d=65536), T=32768, k=1) == -2                # x of 4 GiB or more
 
 
 def test_workspace_query_is_monotone_and_checked():
