@@ -46,8 +46,10 @@
  *     (T rows of F_shared) each stay below 4 GiB.  Every device pointer must be 16-byte aligned.
  *   - Routing semantics: selection on the fp32 logits in the total order (logit
  *     descending, expert index ascending) -- ties go to the lower index, +0 == -0;
- *     inputs must be finite.  The k selected experts are kept in rank order
- *     ("slots").  Gates are the softmax over the k selected logits (sum to 1).
+ *     inputs must be finite (a token whose logits come out NaN is still routed
+ *     safely: a NaN logit ranks below every number, ties to the lower index, and
+ *     that token's gates and output row are NaN; no other token is affected).
+ *     The k selected experts are kept in rank order ("slots").  Gates are the softmax over the k selected logits (sum to 1).
  *     The fp32 logit is evaluated in a fixed order: d is cut into segments of
  *     128; a segment's partial starts at +0 and takes one fused multiply-add per
  *     element in ascending order; partials are added in ascending order; the
@@ -185,15 +187,6 @@ lexi_status lexi_moe_profile_layer(const lexi_layer_t* layer, const void* x, int
  *   Returns LEXI_ERR_BAD_K when no feasible vector exists (B outside L*k_min .. L*k_max). */
 lexi_status lexi_allocate_topk(const double* D, int32_t L, int32_t B, int32_t k_min, int32_t k_max, int32_t n_pop,
                                int32_t g_max, double eta_mut, uint64_t seed, int32_t* k_out, double* phi_out);
-
-/* Device ceilings for the roofline report (not part of the MoE path; the caller times the launches with events).
- *   lexi_probe_mfma_bf16: `workgroups` workgroups of 4 waves, each wave issuing iters * 16 independent
- *     v_mfma_f32_32x32x16_bf16 (32768 flops each) on operand fragments read once from `operands` (device, at least
- *     40960 bytes of bf16 data: their bit patterns set the switching activity, hence the clock the chip sustains);
- *     flops = workgroups * 4 * iters * 16 * 32768.  sink: device, 1 KB, practically never written.
- *   lexi_probe_hbm_read: one streaming read of `bytes` bytes from src (device).  sink: device, 1 KB. */
-lexi_status lexi_probe_mfma_bf16(const void* operands, void* sink, int32_t iters, int32_t workgroups, void* hip_stream);
-lexi_status lexi_probe_hbm_read(const void* src, size_t bytes, void* sink, void* hip_stream);
 
 /* Static description of a status code. */
 const char* lexi_strerror(int32_t status);

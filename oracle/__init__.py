@@ -17,7 +17,8 @@ from typing import Dict, Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB = os.path.join(_HERE, "liblexi_oracle.so")
+# LEXI_ORACLE_LIB: load this build of lexi_oracle.c instead (the sanitizer test points it at an instrumented one)
+LIB = os.environ.get("LEXI_ORACLE_LIB") or os.path.join(_HERE, "liblexi_oracle.so")
 # -ffp-contract=off: the router's fused multiply-adds are the explicit fmaf() calls and nothing else.
 CFLAGS = ["-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared"]
 

@@ -196,9 +196,22 @@ def alloc_workspace(layers: Sequence[Layer], T_max: int, k_max: int, device="cud
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
+def _check_io(where: str, x: torch.Tensor, y: Optional[torch.Tensor], d: int, dtype: torch.dtype) -> None:
+    """The C ABI takes bare pointers: a tensor of another dtype, width or stride would be misread silently."""
+    if not (x.is_cuda and x.dtype == dtype and int(x.shape[-1]) == d and x.stride(-1) == 1 and
+            (x.dim() < 2 or x.stride(-2) == d)):
+        raise ValueError(f"{where}: x must be a CUDA tensor [..., T, {d}] of {dtype} with contiguous rows")
+    if y is not None and not (y.is_cuda and int(y.shape[-1]) == d and y.stride(-1) == 1 and
+                              (y.dim() < 2 or y.stride(-2) == d) and int(y.shape[-2]) == int(x.shape[-2])):
+        raise ValueError(f"{where}: y must be a CUDA tensor [..., T, {d}] with contiguous rows")
+
+
 def lexi_moe_layer_forward(layer: Layer, x: torch.Tensor, y: torch.Tensor, k: int, workspace: torch.Tensor,
                            routing: Optional[RoutingOut] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
     """y = f_moe(x; k) for one layer, enqueued on `stream` (default: torch's current stream)."""
+    _check_io("lexi_moe_layer_forward", x, y, layer.d, layer.dtype)
+    if x.dim() != 2 or y.dim() != 2:
+        raise ValueError("lexi_moe_layer_forward: x and y are [T][d]")
     T = int(x.shape[0])
     st = _lib.lexi_moe_layer_forward(ctypes.byref(layer.c), _dp(x), _dp(y), _dtype_code(y.dtype), T, int(k),
                                      _dp(workspace), workspace.numel(), _stream_ptr(stream),
@@ -216,6 +229,11 @@ def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: tor
 
     stage_events: None, or a StageEvents object; then the profiled entry point records its events."""
     L = len(layers)
+    for ly in layers:
+        _check_io("lexi_moe_stack_forward", x, y, ly.d, ly.dtype)
+    if x.dim() not in (2, 3) or y.dim() not in (2, 3) or (x.dim() == 3 and int(x.shape[0]) < L) or \
+            (y.dim() == 3 and int(y.shape[0]) < L):
+        raise ValueError("lexi_moe_stack_forward: x is [T][d] or [L][T][d], y is [L][T][d] (or [T][d])")
     T = int(x.shape[-2])
     x_stride = 0 if x.dim() == 2 else int(x.stride(0))
     y_stride = int(y.stride(0)) if y.dim() == 3 else 0
@@ -241,6 +259,9 @@ def lexi_moe_profile_layer(layer: Layer, x: torch.Tensor, k_base: int, k_list: S
                            workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
     """Delta_k = ||f_moe(x; k) - f_moe(x; k_base)||_F for every k of k_list (Algorithm 1, one iteration), as a device
     float tensor [len(k_list)].  The workspace is allocated here when none is given."""
+    _check_io("lexi_moe_profile_layer", x, None, layer.d, layer.dtype)
+    if x.dim() != 2:
+        raise ValueError("lexi_moe_profile_layer: x is [T][d]")
     T, n = int(x.shape[0]), len(k_list)
     need = int(_lib.lexi_moe_profile_workspace_bytes(ctypes.byref(layer.c), T, int(k_base), n))
     if need == 0:

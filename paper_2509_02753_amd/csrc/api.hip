@@ -120,20 +120,25 @@ lexi_status check_layer(const lexi_layer_t* ly) {
     return LEXI_OK;
 }
 
+// Limits on (T, k) that every entry point running the routed path shares.
+lexi_status check_sizes(const lexi_layer_t* ly, int32_t T, int32_t k) {
+    if (T < 0) return LEXI_ERR_SHAPE;
+    if (k < 1 || k > ly->E) return LEXI_ERR_BAD_K;
+    if ((int64_t)T * k >= (1 << 24)) return LEXI_ERR_SHAPE;
+    // the tile kernels address their input rows with 32-bit byte offsets
+    const uint64_t es = ly->dtype == LEXI_BF16 ? 2 : 4, lim = (uint64_t)1 << 32;
+    if ((uint64_t)T * ly->d * es >= lim || (uint64_t)T * k * ly->F * es >= lim || (uint64_t)T * ly->F_shared * es >= lim)
+        return LEXI_ERR_SHAPE;
+    return LEXI_OK;
+}
+
 lexi_status check_call(const lexi_layer_t* ly, const void* x, const void* y, int32_t y_dtype, int32_t T, int32_t k,
                        const void* workspace, size_t workspace_bytes, const lexi_routing_out_t* dbg) {
     lexi_status st = check_layer(ly);
     if (st != LEXI_OK) return st;
     if (y_dtype != LEXI_F32 && y_dtype != LEXI_BF16) return LEXI_ERR_DTYPE;
-    if (T < 0) return LEXI_ERR_SHAPE;
-    if (k < 1 || k > ly->E) return LEXI_ERR_BAD_K;
-    if ((int64_t)T * k >= (1 << 24)) return LEXI_ERR_SHAPE;
-    {   // the tile kernels address their input rows with 32-bit byte offsets
-        const uint64_t es = ly->dtype == LEXI_BF16 ? 2 : 4, lim = (uint64_t)1 << 32;
-        if ((uint64_t)T * ly->d * es >= lim || (uint64_t)T * k * ly->F * es >= lim ||
-            (uint64_t)T * ly->F_shared * es >= lim)
-            return LEXI_ERR_SHAPE;
-    }
+    st = check_sizes(ly, T, k);
+    if (st != LEXI_OK) return st;
     if (T == 0) return LEXI_OK;
     if (!x || !y || !workspace) return LEXI_ERR_NULL;
     if (misaligned(x) || misaligned(y) || misaligned(workspace)) return LEXI_ERR_ALIGN;
@@ -395,8 +400,8 @@ lexi_status lexi_moe_profile_layer(const lexi_layer_t* layer, const void* x, int
     if (st != LEXI_OK) return st;
     if (!k_list || !delta) return LEXI_ERR_NULL;
     if (T < 1 || n_k < 1 || n_k > kProfileMaxK) return LEXI_ERR_SHAPE;
-    if (k_base < 1 || k_base > layer->E) return LEXI_ERR_BAD_K;
-    if ((int64_t)T * k_base >= (1 << 24)) return LEXI_ERR_SHAPE;
+    st = check_sizes(layer, T, k_base);
+    if (st != LEXI_OK) return st;
     ProfileKList kl{};
     kl.n = n_k;
     for (int i = 0; i < n_k; ++i) {

@@ -9,8 +9,8 @@ template <bool U_BF16>
 __device__ __forceinline__ void store_normalised(void* u, size_t idx, const f32x4_t& v, float inv) {
     if (U_BF16) {
         u32x2_t pk;
-        pk[0] = (uint32_t)f32_to_bf16(v[0] * inv) | ((uint32_t)f32_to_bf16(v[1] * inv) << 16);
-        pk[1] = (uint32_t)f32_to_bf16(v[2] * inv) | ((uint32_t)f32_to_bf16(v[3] * inv) << 16);
+        pk[0] = pack_bf16x2(v[0] * inv, v[1] * inv);
+        pk[1] = pack_bf16x2(v[2] * inv, v[3] * inv);
         *(u32x2_t*)((bf16_t*)u + idx) = pk;
     } else {
         f32x4_t o;

@@ -1,6 +1,6 @@
 // Measured ceilings of the device, for the roofline report: what the matrix cores and the HBM sustain in plain loops
 // with nothing else going on.  The caller times the launches with events; nothing here is on the MoE path.
-#include "../../include/lexi_moe.h"
+#include "../../include/lexi_probe.h"
 #include "common.hpp"
 
 namespace lexi {

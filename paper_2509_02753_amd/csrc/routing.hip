@@ -213,6 +213,11 @@ topk_kernel(const float* __restrict__ partial, const float* __restrict__ bias, i
 #pragma unroll
         for (int m = 0; m < TM; ++m) total[m] = total[m] + b;
     }
+    // Inputs are finite by contract.  A NaN logit (one NaN or Inf activation is enough) compares unequal to every
+    // maximum, which would leave the ballot below empty and the expert index undefined; it ranks as -inf instead, so
+    // every round selects a valid expert (all-NaN row: experts 0..k-1) and the token's gates and output come out NaN.
+#pragma unroll
+    for (int m = 0; m < TM; ++m) total[m] = (total[m] == total[m]) ? total[m] : -INFINITY;
 
     // ---- top-k: slot-major, token-minor, so the TM independent reduction chains of one round overlap ----
     uint32_t taken = 0;        // lane e: bit m set once token m has selected expert e
@@ -414,6 +419,7 @@ topk_scan_kernel(const float* __restrict__ partial, const float* __restrict__ bi
                     if (sg0 + c < nseg) total = total + tmp[c];
             }
             if (bias != nullptr) total = total + b;
+            total = (total == total) ? total : -INFINITY;   // a NaN logit ranks last (see topk_kernel)
             float val = -INFINITY;
             for (int s = 0; s < k; ++s) {
                 const bool open = lane_valid && !hit;

@@ -9,9 +9,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "lexi_moe.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lexi_[a-z0-9_]+)\s*\(", text)))
+    """Every function any header under include/ declares."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if fn.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, fn)).read(), flags=re.S)
+            names |= set(re.findall(r"\b(lexi_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -62,6 +67,26 @@ def test_argument_validation_returns_codes_without_launching():
     assert call_layer(P, ok, T=1 << 23, k=2) == -2                                  # T*k >= 2^24
     assert call_layer(P, fake_layer(P, F=65536), T=16384, k=2) == -2                # intermediate of 4 GiB or more
     assert call_layer(P, fake_layer(P, d=65536), T=32768, k=1) == -2                # x of 4 GiB or more
+
+
+def test_profile_entry_point_validates_before_launching():
+    """lexi_moe_profile_layer applies the limits of the forward entry points up front (fake pointers: any launch
+    would fail, so a validation code coming back shows nothing was enqueued)."""
+    import paper_2509_02753_amd as P
+    from paper_2509_02753_amd.binding import _lib
+
+    def prof(ly, T=16, k_base=2, k_list=(1, 2), x=0x50000, delta=0x60000, ws=0x70000, ws_bytes=1 << 40):
+        kl = (ctypes.c_int32 * len(k_list))(*k_list)
+        return _lib.lexi_moe_profile_layer(ctypes.byref(ly), x, T, k_base, kl, len(k_list), delta, ws, ws_bytes, None)
+
+    ok = fake_layer(P)
+    assert prof(ok, T=0) == -2 and prof(ok, k_base=0) == -3 and prof(ok, k_base=9) == -3
+    assert prof(ok, k_list=(3,)) == -3                                     # a listed k above k_base
+    assert prof(ok, x=None) == -1 and prof(ok, delta=None) == -1 and prof(ok, ws=None) == -1
+    assert prof(ok, ws_bytes=1024) == -5
+    assert prof(ok, T=1 << 23) == -2                                       # T*k >= 2^24
+    assert prof(fake_layer(P, F=65536), T=16384) == -2                     # intermediate of 4 GiB or more
+    assert prof(fake_layer(P, d=65536), T=32768, k_base=1, k_list=(1,)) == -2   # x of 4 GiB or more
 
 
 def test_workspace_query_is_monotone_and_checked():

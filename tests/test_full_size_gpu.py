@@ -2,9 +2,12 @@
 real shapes and token counts through lexi_moe_stack_forward with its per-layer k vector.
 
 Routing (selected experts, gates, counts, offsets, permutation) is compared with the oracle for EVERY token of EVERY
-layer.  Outputs are compared on 64 sampled tokens per layer, which the oracle computes one by one: the first, middle
-and last token, the eight tokens whose k-th and (k+1)-th logits lie closest together, one token of every expert that
-received any, and seeded random ones.  Every layer is output-checked; a layer's weights are regenerated on the host
+layer.  Outputs are compared on sampled tokens of every layer, which the oracle computes one by one: the first, middle
+and last token, the eight tokens whose k-th and (k+1)-th logits lie closest together, the first and the last row of
+every expert's group (the last row lies in the group's ragged last token tile), and seeded random ones up to 64 (more
+when the groups' ends alone exceed that).  The error against the oracle WITHOUT the bf16 rounding of the SwiGLU
+intermediate is printed beside the graded one (reported, not asserted: it measures the bf16 storage of the
+intermediate, which both sides of the graded comparison share).  Every layer is output-checked; a layer's weights are regenerated on the host
 from the same seeded streams, used for all token counts of the workload, and dropped.
 """
 import numpy as np
@@ -29,7 +32,9 @@ def _sample_tokens(routing, T, k, E, seed):
         picked.update(np.argsort(gap, kind="stable")[:N_NEAR_TIE].tolist())
     for e in range(E):
         if routing.counts[e] > 0:
+            # first and last row of the expert's group: the last row sits in the group's ragged last token tile
             picked.add(int(routing.perm[routing.offsets[e]]) // k)
+            picked.add(int(routing.perm[routing.offsets[e + 1] - 1]) // k)
     rng = np.random.default_rng(seed)
     for t in rng.permutation(T).tolist():
         if len(picked) >= min(T, N_SAMPLE):
@@ -77,6 +82,7 @@ def _check_workload(cfg, Ts, ffn_layers=None):
         del y2, x, ws
         runs[T] = (y, routs)
     worst = {T: 0.0 for T in Ts}
+    worst_unrounded = {T: 0.0 for T in Ts}
     for l in range(L):
         k = int(kvec[l])
         with_ffn = l in ffn_layers
@@ -93,12 +99,16 @@ def _check_workload(cfg, Ts, ffn_layers=None):
                 err = rel_err(got, ref.out)
                 worst[T] = max(worst[T], err)
                 assert err <= TOL_BF16, f"layer {l} T={T}: output error {err:.3e}"
+                if l % 4 == 0:   # reported only: the same tokens against the fp64 oracle with no intermediate rounding
+                    ref_u = O.moe_layer(host, xh, k, tokens=tok, round_act=False)
+                    worst_unrounded[T] = max(worst_unrounded[T], rel_err(got, ref_u.out))
         del host
         if l % 4 == 3 or l == L - 1:
             _progress(f"[full-size] {cfg.name}: layers 0..{l} checked")
     for T in Ts:
         _progress(f"[full-size] {cfg.name} T={T}: routing exact on {L} layers, outputs on {len(ffn_layers)} layers x "
-                  f"{min(T, N_SAMPLE)} tokens, worst error {worst[T]:.2e}")
+                  f">= {min(T, N_SAMPLE)} tokens, worst error {worst[T]:.2e} (against the oracle without the bf16 rounding "
+                  f"of the SwiGLU intermediate, every 4th layer: {worst_unrounded[T]:.2e})")
 
 
 class _RoutingCfg:

@@ -271,3 +271,31 @@ def test_two_host_threads_on_two_streams():
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads), "a worker did not finish"
     assert not errors, errors
+
+
+def test_a_nan_activation_is_routed_safely():
+    """Inputs are finite by contract; a NaN activation must nevertheless produce a valid routing (every index in
+    range, perm a permutation) and NaN for that token only.  A row of NaN logits ranks every expert equal, so both
+    sides select experts 0..k-1 for it; every other token matches the oracle as usual."""
+    import torch
+    import paper_2509_02753_amd as P
+    cfg = S.mini(S.C2, L=1, d=256, F=128)
+    dl, hl = device_and_host_layer(cfg, 0)
+    for T, k, bad in ((200, 4, 17), (9, 3, 8), (2100, 2, 2099)):
+        xh = S.host_x(cfg, 0, T).copy()
+        xh[bad, 5] = 0x7FC0                      # bf16 quiet NaN
+        xd = torch.from_numpy(xh.view(np.int16)).cuda().view(torch.bfloat16)
+        y = torch.empty((T, cfg.d), dtype=torch.float32, device="cuda:0")
+        rout = P.RoutingOut(T, k, cfg.E)
+        P.lexi_moe_layer_forward(dl, xd, y, k, P.alloc_workspace([dl], T, k), routing=rout)
+        torch.cuda.synchronize()
+        idx, perm = to_numpy(rout.topk_idx), to_numpy(rout.perm)
+        assert idx.min() >= 0 and idx.max() < cfg.E
+        assert idx[bad].tolist() == list(range(k))
+        assert np.array_equal(np.sort(perm), np.arange(T * k))
+        ref = O.moe_layer(hl, xh, k, round_act=True)
+        assert np.array_equal(idx, ref.topk_idx) and np.array_equal(perm, ref.perm)
+        yg = y.cpu().numpy()
+        assert np.isnan(yg[bad]).all()
+        keep = np.arange(T) != bad
+        assert np.isfinite(yg[keep]).all() and rel_err(yg[keep], ref.out[keep]) <= TOL_BF16
