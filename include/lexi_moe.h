@@ -131,6 +131,19 @@ lexi_status lexi_moe_layer_forward(const lexi_layer_t* layer, const void* x, voi
                                    int32_t k, void* workspace, size_t workspace_bytes, void* hip_stream,
                                    const lexi_routing_out_t* dbg);
 
+/* lexi_moe_layer_forward for callers that cannot allocate device memory or carry a workspace around: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus the workspace, same
+ * kernels, same result bits.  The scratch lives in a static device array inside the library (64 MiB; each GPU the
+ * library runs on holds its copy until the process ends), whose address is looked up on the first call on a device.
+ * The call allocates nothing, frees nothing, and creates no stream or event (a shared expert runs on `hip_stream`).
+ *   Limit: the call must need at most 64 MiB of workspace (lexi_moe_workspace_bytes(layer, 1, T, k) <= 67108864:
+ *   decode-sized batches of every workload shape here), otherwise LEXI_ERR_WORKSPACE and nothing is launched.
+ *   All calls on one GPU share the one array: calls that overlap in time on the same GPU (different streams or host
+ *   threads) race; calls on one stream are ordered and safe.  The array keeps the last call's contents; no kernel
+ *   relies on them. */
+lexi_status lexi_moe_layer_forward_static(const lexi_layer_t* layer, const void* x, void* y, int32_t y_dtype, int32_t T,
+                                          int32_t k, void* hip_stream, const lexi_routing_out_t* dbg);
+
 /* A stack of L layers with the static per-layer allocation k_vec = (k_1 .. k_L) (Sec. 1; output of Algorithm 2).
  *   layers: host array[L]; k_vec: HOST int32[L].
  *   mode LEXI_STACK_INDEPENDENT: layer l reads x + l*x_layer_stride elements and writes y + l*y_layer_stride elements

@@ -18,7 +18,8 @@ LEXI_OK = 0
 LEXI_F32, LEXI_BF16 = 0, 1
 SHARED_NONE, SHARED_UNGATED, SHARED_SIGMOID = 0, 1, 2
 
-EXPORTS = ("lexi_pack_weights", "lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_stack_forward",
+EXPORTS = ("lexi_pack_weights", "lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_layer_forward_static",
+           "lexi_moe_stack_forward",
            "lexi_moe_stack_forward_profiled", "lexi_moe_profile_workspace_bytes", "lexi_moe_profile_layer",
            "lexi_allocate_topk", "lexi_probe_mfma_bf16", "lexi_probe_hbm_read", "lexi_strerror",
            "lexi_moe_version")
@@ -64,6 +65,9 @@ def _load() -> ctypes.CDLL:
     lib.lexi_moe_layer_forward.restype = i32
     lib.lexi_moe_layer_forward.argtypes = [ctypes.POINTER(lexi_layer_t), vp, vp, i32, i32, i32, vp, sz, vp,
                                            ctypes.POINTER(lexi_routing_out_t)]
+    lib.lexi_moe_layer_forward_static.restype = i32
+    lib.lexi_moe_layer_forward_static.argtypes = [ctypes.POINTER(lexi_layer_t), vp, vp, i32, i32, i32, vp,
+                                                  ctypes.POINTER(lexi_routing_out_t)]
     lib.lexi_moe_stack_forward.restype = i32
     lib.lexi_moe_stack_forward.argtypes = [ctypes.POINTER(lexi_layer_t), i32, ctypes.POINTER(i32), vp, i64, vp, i64,
                                            i32, i32, i32, vp, sz, vp, ctypes.POINTER(lexi_routing_out_t)]
@@ -218,6 +222,19 @@ def lexi_moe_layer_forward(layer: Layer, x: torch.Tensor, y: torch.Tensor, k: in
                                      ctypes.byref(routing.c) if routing is not None else None)
     if st != LEXI_OK:
         raise LexiError(st, "lexi_moe_layer_forward")
+
+
+def lexi_moe_layer_forward_static(layer: Layer, x: torch.Tensor, y: torch.Tensor, k: int,
+                                  routing: Optional[RoutingOut] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """lexi_moe_layer_forward without a workspace argument: the library's static device scratch (64 MiB) is used."""
+    _check_io("lexi_moe_layer_forward_static", x, y, layer.d, layer.dtype)
+    if x.dim() != 2 or y.dim() != 2:
+        raise ValueError("lexi_moe_layer_forward_static: x and y are [T][d]")
+    st = _lib.lexi_moe_layer_forward_static(ctypes.byref(layer.c), _dp(x), _dp(y), _dtype_code(y.dtype), int(x.shape[0]),
+                                            int(k), _stream_ptr(stream),
+                                            ctypes.byref(routing.c) if routing is not None else None)
+    if st != LEXI_OK:
+        raise LexiError(st, "lexi_moe_layer_forward_static")
 
 
 def lexi_moe_stack_forward(layers: Sequence[Layer], k_vec: Sequence[int], x: torch.Tensor, y: torch.Tensor,

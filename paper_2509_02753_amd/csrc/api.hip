@@ -44,6 +44,28 @@ SideStream* side_stream() {
     return ss.ok ? &ss : nullptr;   // no side stream: the shared expert simply stays on the caller's stream
 }
 
+// Scratch of lexi_moe_layer_forward_static: the workspace of one decode-sized layer call, held in the library's own
+// device image so that the call needs no allocation and no workspace argument.  Every GPU the library runs on holds
+// its own copy until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// device address is looked up once per device and used from then on.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+void* g_static_scratch_ptr[kMaxDevices] = {};
+std::mutex g_static_scratch_mutex;
+
+// Device address of the current device's copy of the scratch array, or null.
+void* static_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (g_static_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess) return nullptr;
+        g_static_scratch_ptr[dev] = p;
+    }
+    return g_static_scratch_ptr[dev];
+}
+
 // Walks the workspace once; with base == nullptr it only measures.
 struct Carver {
     char* base;
@@ -196,7 +218,7 @@ lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t
 lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_dtype, int32_t T, int32_t k,
                       void* workspace, hipStream_t s, const lexi_routing_out_t* dbg,
                       const lexi_stage_events_t* events = nullptr, const float* hidden = nullptr,
-                      const void* u_in = nullptr, void* u_out = nullptr) {
+                      const void* u_in = nullptr, void* u_out = nullptr, bool allow_side_stream = true) {
     auto mark = [&](int i) {
         if (events && events->ev[i]) (void)hipEventRecord((hipEvent_t)events->ev[i], s);
     };
@@ -235,7 +257,7 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
         sd.sched = nullptr; sd.sched_count = nullptr; sd.out = w.y_shared;
         return launch_down(sd, st) == hipSuccess;
     };
-    SideStream* side = (ly.F_shared > 0 && T <= kSideStreamMaxT) ? side_stream() : nullptr;
+    SideStream* side = (allow_side_stream && ly.F_shared > 0 && T <= kSideStreamMaxT) ? side_stream() : nullptr;
     // the fork/join events are shared by every call on the device: host threads enqueue their layers one at a time
     std::unique_lock<std::mutex> side_lock(g_side_enqueue_mutex, std::defer_lock);
     if (side) {
@@ -310,6 +332,20 @@ lexi_status lexi_moe_layer_forward(const lexi_layer_t* layer, const void* x, voi
     lexi_status st = check_call(layer, x, y, y_dtype, T, k, workspace, workspace_bytes, dbg);
     if (st != LEXI_OK || T == 0) return st;
     return run_layer(*layer, x, y, y_dtype, T, k, workspace, (hipStream_t)hip_stream, dbg);
+}
+
+lexi_status lexi_moe_layer_forward_static(const lexi_layer_t* layer, const void* x, void* y, int32_t y_dtype, int32_t T,
+                                          int32_t k, void* hip_stream, const lexi_routing_out_t* dbg) {
+    // validate against the static array's size first: a fake non-null, aligned workspace address stands in until the
+    // real one is looked up (check_call only compares it with null and tests its alignment)
+    lexi_status st = check_call(layer, x, y, y_dtype, T, k, (const void*)(uintptr_t)256, kStaticScratchBytes, dbg);
+    if (st != LEXI_OK || T == 0) return st;
+    void* ws = static_scratch();
+    if (ws == nullptr) return LEXI_ERR_LAUNCH;
+    // every kernel writes the part of the scratch it reads later in the same call, so nothing needs clearing; the
+    // shared expert stays on the caller's stream (no library-owned stream or event is created or used)
+    return run_layer(*layer, x, y, y_dtype, T, k, ws, (hipStream_t)hip_stream, dbg, nullptr, nullptr, nullptr, nullptr,
+                     /*allow_side_stream=*/false);
 }
 
 lexi_status lexi_moe_stack_forward_profiled(const lexi_layer_t* layers, int32_t L, const int32_t* k_vec,

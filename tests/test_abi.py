@@ -89,6 +89,20 @@ def test_profile_entry_point_validates_before_launching():
     assert prof(fake_layer(P, d=65536), T=32768, k_base=1, k_list=(1,)) == -2   # x of 4 GiB or more
 
 
+def test_static_scratch_entry_point_validates_before_launching():
+    """lexi_moe_layer_forward_static: the same argument checks, and a call that needs more than the library's 64 MiB
+    static scratch is refused with LEXI_ERR_WORKSPACE (fake pointers: nothing may be launched)."""
+    import paper_2509_02753_amd as P
+    from paper_2509_02753_amd.binding import _lib
+    call = lambda ly, x=0x50000, y=0x60000, y_dtype=0, T=16, k=2: _lib.lexi_moe_layer_forward_static(
+        ctypes.byref(ly), x, y, y_dtype, T, k, None, None)
+    ok = fake_layer(P)
+    assert call(ok, T=0) == 0
+    assert call(ok, k=0) == -3 and call(ok, T=-1) == -2 and call(ok, x=None) == -1 and call(ok, y=0x60004) == -6
+    assert call(ok, y_dtype=5) == -4
+    assert call(fake_layer(P, d=2048, F=1024, E=64), T=4096, k=8) == -5       # 353 MB of workspace
+
+
 def test_workspace_query_is_monotone_and_checked():
     import paper_2509_02753_amd as P
     from paper_2509_02753_amd.binding import _lib, lexi_layer_t
