@@ -16,6 +16,14 @@ extern "C" {
 lexi_status lexi_probe_mfma_bf16(const void* operands, void* sink, int32_t iters, int32_t workgroups, void* hip_stream);
 lexi_status lexi_probe_hbm_read(const void* src, size_t bytes, void* sink, void* hip_stream);
 
+/* Which schedule the down GEMM of lexi_moe_layer_forward(layer, T, k) into an independent output takes (a diagnostic
+ * for tests and profiles; the choice never changes what is computed, only where the partial sums are added).
+ *   which = 0: the routed experts' down GEMM; which = 1: the shared expert's.
+ *   Returns 0 = weight-streaming schedule (decode-sized), 1 = tile schedule, 2 = tile schedule with the reduction cut
+ *   in two (two partial planes, added by the combine), 3 = tile schedule storing the output rows directly (k = 1 and
+ *   nothing else to add: no combine pass); -1 = invalid arguments or no shared expert. */
+int32_t lexi_moe_down_plan(const lexi_layer_t* layer, int32_t T, int32_t k, int32_t which);
+
 #ifdef __cplusplus
 }
 #endif

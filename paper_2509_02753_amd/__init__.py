@@ -6,7 +6,7 @@ first use (so `python -m paper_2509_02753_amd.build` can still run to create it)
 """
 _API = ["EXPORTS", "LEXI_BF16", "LEXI_F32", "LIB_PATH", "SHARED_NONE", "SHARED_SIGMOID", "SHARED_UNGATED", "Layer",
         "LexiError", "RoutingOut", "lexi_allocate_topk", "STAGE_NAMES", "StageEvents", "alloc_workspace", "lexi_moe_layer_forward", "lexi_moe_layer_forward_static",
-        "lexi_pack_weights", "lexi_moe_profile_layer", "lexi_moe_stack_forward", "lexi_moe_workspace_bytes", "lexi_probe_hbm_read",
+        "lexi_pack_weights", "lexi_moe_profile_layer", "lexi_moe_stack_forward", "lexi_moe_workspace_bytes", "lexi_probe_hbm_read", "lexi_moe_down_plan",
         "lexi_probe_mfma_bf16", "strerror", "version"]
 __all__ = list(_API)
 

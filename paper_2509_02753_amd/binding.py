@@ -21,7 +21,7 @@ SHARED_NONE, SHARED_UNGATED, SHARED_SIGMOID = 0, 1, 2
 EXPORTS = ("lexi_pack_weights", "lexi_moe_workspace_bytes", "lexi_moe_layer_forward", "lexi_moe_layer_forward_static",
            "lexi_moe_stack_forward",
            "lexi_moe_stack_forward_profiled", "lexi_moe_profile_workspace_bytes", "lexi_moe_profile_layer",
-           "lexi_allocate_topk", "lexi_probe_mfma_bf16", "lexi_probe_hbm_read", "lexi_strerror",
+           "lexi_allocate_topk", "lexi_probe_mfma_bf16", "lexi_probe_hbm_read", "lexi_moe_down_plan", "lexi_strerror",
            "lexi_moe_version")
 N_STAGE_EVENTS = 6
 STAGE_NAMES = ("routing", "gate_up", "down", "shared", "combine")
@@ -84,6 +84,8 @@ def _load() -> ctypes.CDLL:
     lib.lexi_probe_mfma_bf16.argtypes = [vp, vp, i32, i32, vp]
     lib.lexi_probe_hbm_read.restype = i32
     lib.lexi_probe_hbm_read.argtypes = [vp, sz, vp, vp]
+    lib.lexi_moe_down_plan.restype = i32
+    lib.lexi_moe_down_plan.argtypes = [ctypes.POINTER(lexi_layer_t), i32, i32, i32]
     lib.lexi_strerror.restype = ctypes.c_char_p
     lib.lexi_strerror.argtypes = [i32]
     lib.lexi_moe_version.restype = ctypes.c_char_p
@@ -309,6 +311,12 @@ def lexi_allocate_topk(D, B: int, k_min: int, k_max: int, n_pop: int = 32, g_max
     if st != LEXI_OK:
         raise LexiError(st, "lexi_allocate_topk")
     return list(out), phi.value
+
+
+def lexi_moe_down_plan(layer: Layer, T: int, k: int, shared: bool = False) -> int:
+    """Schedule of the (routed or shared) down GEMM of a call: 0 streaming, 1 tiles, 2 tiles with the reduction cut in
+    two, 3 tiles storing the output rows directly; -1 if there is no such GEMM."""
+    return int(_lib.lexi_moe_down_plan(ctypes.byref(layer.c), int(T), int(k), 1 if shared else 0))
 
 
 def lexi_probe_mfma_bf16(operands: torch.Tensor, sink: torch.Tensor, iters: int, workgroups: int,

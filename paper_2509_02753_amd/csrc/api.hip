@@ -15,6 +15,26 @@ constexpr int kStreamDenseRows = 64;      // token count at or below which the s
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Split of the down GEMM's reduction dimension on the tile schedule.  A launch runs (token tiles x column blocks of
+// 256 features) work items on 512 workgroup slots (two per CU).  When a launch with a long reduction cannot fill
+// those slots even once, cutting the reduction in two gives twice as many items of half the length; the halves land
+// in two planes of the output that the consumer adds.  Eligible: at least 32 K-steps of 64, an even number of them.
+// Taken when the expected number of items (full tiles plus half a ragged tile per expert; the real number is only
+// known on the device) is at most half the slots and the time saved outweighs writing and re-reading the second
+// plane.  (For launches of several rounds, e.g. 1100 items of 14336, the split measured no gain in the down GEMM and
+// cost the combine a second plane, so it is not taken there.)
+constexpr int kWorkgroupSlots = 512;
+inline bool ksplit_eligible(int K) { return K / 64 >= 32 && (K / 64) % 2 == 0; }
+int choose_ksplit(int64_t rows, int groups, int K, int features, bool is_bf16) {
+    if (!is_bf16 || !ksplit_eligible(K) || rows <= 0) return 1;
+    const double ragged = groups > 1 ? 0.5 * (double)(groups < rows ? groups : rows) : (rows % kTileTokens ? 0.5 : 0.0);
+    const double items = ((double)(rows / kTileTokens) + ragged) * ((features + 255) / 256);
+    if (items > kWorkgroupSlots / 2) return 1;
+    const double t_item = (2.0 * kTileTokens * 256.0 * K) / 3.9e12;           // one item at what one CU sustains
+    const double t_plane = 2.0 * (double)rows * features * 4.0 / 5.0e12;      // second plane: written once, read once
+    return 0.5 * t_item > 1.5 * t_plane ? 2 : 1;
+}
+
 // The shared expert depends on x only, not on the routing, so for decode-sized batches (where its kernels are short
 // and latency-bound) it runs on a side stream that forks from the caller's stream at the start of the layer and joins
 // it again in front of the combine.  One side stream and one event pair per device, created on first use and kept
@@ -85,6 +105,8 @@ struct Workspace {
     float *gates, *partial, *y_slot, *y_shared;
     void *act, *act_shared, *u;
     int max_tiles;
+    int slot_planes = 1, shared_planes = 1;   // planes of y_slot / y_shared the last launches wrote
+    bool direct = false;                      // the routed down GEMM wrote the layer's output itself
     size_t bytes;
 };
 
@@ -112,10 +134,13 @@ Workspace carve(const lexi_layer_t& ly, int T, int k, void* base) {
     w.sched = c.take<int32_t>((size_t)w.max_tiles * 8);
     w.sched_count = c.take<int32_t>(4);
     w.act = c.take<char>(A * ly.F * es);
-    w.y_slot = c.take<float>(A * ly.d);
+    // two planes wherever the down GEMM may split its reduction (independent of T and k, so that the size asked for
+    // at (T_max, k_max) covers every smaller call)
+    const bool bf = ly.dtype == LEXI_BF16;
+    w.y_slot = c.take<float>(A * ly.d * ((bf && ksplit_eligible(ly.F)) ? 2 : 1));
     if (ly.F_shared > 0) {
         w.act_shared = c.take<char>((size_t)T * ly.F_shared * es);
-        w.y_shared = c.take<float>((size_t)T * ly.d);
+        w.y_shared = c.take<float>((size_t)T * ly.d * ((bf && ksplit_eligible(ly.F_shared)) ? 2 : 1));
     }
     w.bytes = align_up(c.used, 256);
     return w;
@@ -174,8 +199,35 @@ lexi_status check_call(const lexi_layer_t* ly, const void* x, const void* y, int
 }
 
 // Routing and the routed expert GEMMs of one layer at top-k = k: fills the routing arrays, act and y_slot of `w`.
+// `allow_split`: the down GEMM may write two planes of y_slot (w.slot_planes tells).  `direct_y` != null (k == 1, nothing
+// else to add): the down GEMM stores the output rows straight into the layer's output (w.direct tells whether it did).
+// Launch plan of the down GEMMs of one call (also what lexi_moe_down_plan reports).
+struct DownPlan {
+    bool routed_streams, shared_streams;   // weight-streaming schedule instead of the tile schedule
+    int routed_ksplit, shared_ksplit;      // parts of the reduction on the tile schedule (1 or 2)
+    bool routed_direct;                    // with k == 1 and nothing to add: rows stored straight into y
+};
+DownPlan plan_down(const lexi_layer_t& ly, int32_t T, int32_t k, bool allow_split, bool allow_direct) {
+    DownPlan p{};
+    const bool bf = ly.dtype == LEXI_BF16;
+    const int64_t A = (int64_t)T * k;
+    const int max_tiles = (int)(A / kTileTokens) + (int)(A < ly.E ? A : ly.E);
+    const bool stream_routed = A <= (int64_t)kStreamRowsPerExpert * ly.E;
+    // the down projection has few column blocks (d / 256): with few token tiles as well the tile schedule would leave
+    // most CUs idle, so it streams too (16-feature units, K split over the waves)
+    p.routed_streams = stream_routed || (int64_t)max_tiles * ((ly.d + 255) / 256) <= kStreamDownMaxItems;
+    p.shared_streams = T <= kStreamDenseRows;
+    p.routed_ksplit = p.shared_ksplit = 1;
+    const bool tile_routed = bf && !p.routed_streams;
+    p.routed_direct = tile_routed && allow_direct && k == 1 && ly.F_shared == 0;
+    if (tile_routed && allow_split && !p.routed_direct) p.routed_ksplit = choose_ksplit(A, ly.E, ly.F, ly.d, bf);
+    if (ly.F_shared > 0 && bf && !p.shared_streams) p.shared_ksplit = choose_ksplit(T, 1, ly.F_shared, ly.d, bf);
+    return p;
+}
+
 lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t k, Workspace& w, hipStream_t s,
-                       const lexi_stage_events_t* events) {
+                       const lexi_stage_events_t* events, bool allow_split = true, void* direct_y = nullptr,
+                       bool direct_bf16 = false) {
     auto mark = [&](int i) {
         if (events && events->ev[i]) (void)hipEventRecord((hipEvent_t)events->ev[i], s);
     };
@@ -200,12 +252,17 @@ lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t
     mark(2);
 
     FfnArgs dn{};
-    // the down projection has few column blocks (d / 256): with few token tiles as well the tile schedule would leave
-    // most CUs idle, so it streams too (16-feature units, K split over the waves)
-    dn.streaming = stream_routed || (int64_t)w.max_tiles * ((ly.d + 255) / 256) <= kStreamDownMaxItems;
     dn.is_bf16 = bf; dn.in = w.act; dn.row_token = nullptr; dn.w0 = ly.w_down; dn.w1 = nullptr; dn.K = ly.F;
     dn.features = ly.d; dn.M = T * k; dn.max_tiles = w.max_tiles; dn.tile_tokens = kTileTokens; dn.sched = w.sched;
     dn.sched_count = w.sched_count; dn.out = w.y_slot;
+    const DownPlan plan = plan_down(ly, T, k, allow_split, direct_y != nullptr);
+    dn.streaming = plan.routed_streams;
+    dn.ksplit = w.slot_planes = plan.routed_ksplit;
+    dn.plane_stride = (size_t)T * k * ly.d;
+    w.direct = plan.routed_direct;
+    if (plan.routed_direct) {
+        dn.out = direct_y; dn.scatter = w.row_token; dn.out_bf16 = direct_bf16;
+    }
     if (launch_down(dn, s) != hipSuccess) return LEXI_ERR_LAUNCH;
     mark(3);
     return LEXI_OK;
@@ -255,6 +312,8 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
         sd.is_bf16 = bf; sd.in = w.act_shared; sd.row_token = nullptr; sd.w0 = ly.ws_down; sd.w1 = nullptr;
         sd.K = ly.F_shared; sd.features = ly.d; sd.M = T; sd.max_tiles = dense_tiles; sd.tile_tokens = kTileTokens;
         sd.sched = nullptr; sd.sched_count = nullptr; sd.out = w.y_shared;
+        sd.ksplit = w.shared_planes = plan_down(ly, T, k, true, false).shared_ksplit;
+        sd.plane_stride = (size_t)T * ly.d;
         return launch_down(sd, st) == hipSuccess;
     };
     SideStream* side = (allow_side_stream && ly.F_shared > 0 && T <= kSideStreamMaxT) ? side_stream() : nullptr;
@@ -269,7 +328,9 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
     }
 
     {
-        const lexi_status st = run_routed(ly, x, T, k, w, s, events);
+        // one active expert, nothing else to add, no normalised copy to produce: the down GEMM can write y itself
+        const bool direct = hidden == nullptr && u_out == nullptr;   // (plan_down adds: k == 1, no shared expert, tile schedule)
+        const lexi_status st = run_routed(ly, x, T, k, w, s, events, true, direct ? y : nullptr, y_dtype == LEXI_BF16);
         if (st != LEXI_OK) return st;
     }
 
@@ -281,9 +342,15 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
         }
     }
     mark(4);
+    if (w.direct) {   // y is complete
+        mark(5);
+        return LEXI_OK;
+    }
 
     CombineArgs c{};
     c.y_slot = w.y_slot; c.inv_perm = w.inv_perm; c.gates = w.gates;
+    c.slot_planes = w.slot_planes; c.slot_plane_stride = (size_t)T * k * ly.d;
+    c.shared_planes = w.shared_planes; c.shared_plane_stride = (size_t)T * ly.d;
     c.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr;
     c.x = x; c.x_bf16 = bf;
     c.w_shared_gate = ly.shared_kind == LEXI_SHARED_SIGMOID ? ly.w_shared_gate : nullptr;
@@ -449,7 +516,7 @@ lexi_status lexi_moe_profile_layer(const lexi_layer_t* layer, const void* x, int
     Workspace w = carve(*layer, T, k_base, workspace);
     if (workspace_bytes < w.bytes + align_up((size_t)n_k * T * sizeof(float), 256)) return LEXI_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
-    st = run_routed(*layer, x, T, k_base, w, s, nullptr);
+    st = run_routed(*layer, x, T, k_base, w, s, nullptr, /*allow_split=*/false);
     if (st != LEXI_OK) return st;
     ProfileArgs p{};
     p.y_slot = w.y_slot; p.inv_perm = w.inv_perm; p.gates = w.gates;
@@ -457,6 +524,16 @@ lexi_status lexi_moe_profile_layer(const lexi_layer_t* layer, const void* x, int
     p.part = (float*)((char*)workspace + w.bytes);
     p.delta = delta;
     return launch_profile(p, s) == hipSuccess ? LEXI_OK : LEXI_ERR_LAUNCH;
+}
+
+int32_t lexi_moe_down_plan(const lexi_layer_t* layer, int32_t T, int32_t k, int32_t which) {
+    if (check_layer(layer) != LEXI_OK || T < 1 || k < 1 || k > layer->E) return -1;
+    const DownPlan p = plan_down(*layer, T, k, true, true);
+    switch (which) {
+        case 0: return p.routed_streams ? 0 : (p.routed_direct ? 3 : p.routed_ksplit);
+        case 1: return layer->F_shared == 0 ? -1 : (p.shared_streams ? 0 : p.shared_ksplit);
+        default: return -1;
+    }
 }
 
 const char* lexi_strerror(int32_t status) {

@@ -31,7 +31,8 @@ template <bool Y_BF16, bool X_BF16>
 __global__ void __launch_bounds__(256)
 combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv_perm, const float* __restrict__ gates,
                const float* __restrict__ y_shared, const void* x, const void* __restrict__ w_shared_gate,
-               const float* residual, int d, int k, void* y, void* u_next, float eps) {
+               const float* residual, int d, int k, void* y, void* u_next, float eps, int slot_planes,
+               size_t slot_plane_stride, int shared_planes, size_t shared_plane_stride) {
     __shared__ float wave_part[4];
     const int t = blockIdx.x;
     const int32_t* ip = inv_perm + (size_t)t * k;
@@ -51,13 +52,23 @@ combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv
     for (int j = threadIdx.x * 4; j < d; j += 256 * 4) {
         f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int s = 0; s < k; ++s) {  // slot order = rank order
-            const f32x4_t v = *(const f32x4_t*)(y_slot + (size_t)ip[s] * d + j);
+            f32x4_t v = *(const f32x4_t*)(y_slot + (size_t)ip[s] * d + j);
+            if (slot_planes > 1) {   // the down GEMM's reduction was cut in two: the halves are added first
+                const f32x4_t v1 = *(const f32x4_t*)(y_slot + slot_plane_stride + (size_t)ip[s] * d + j);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = v[i] + v1[i];
+            }
             const float g = gt[s];
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[i] = __builtin_fmaf(g, v[i], acc[i]);
         }
         if (y_shared != nullptr) {
-            const f32x4_t v = *(const f32x4_t*)(y_shared + (size_t)t * d + j);
+            f32x4_t v = *(const f32x4_t*)(y_shared + (size_t)t * d + j);
+            if (shared_planes > 1) {
+                const f32x4_t v1 = *(const f32x4_t*)(y_shared + shared_plane_stride + (size_t)t * d + j);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = v[i] + v1[i];
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[i] = __builtin_fmaf(coef, v[i], acc[i]);
         }
@@ -93,7 +104,8 @@ combine_kernel(const float* __restrict__ y_slot, const int32_t* __restrict__ inv
 template <bool Y_BF16, bool X_BF16>
 static void launch_combine_t(const CombineArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((combine_kernel<Y_BF16, X_BF16>), dim3(a.T), dim3(256), 0, s, a.y_slot, a.inv_perm, a.gates,
-                       a.y_shared, a.x, a.w_shared_gate, a.residual, a.d, a.k, a.y, a.u_next, kRmsEps);
+                       a.y_shared, a.x, a.w_shared_gate, a.residual, a.d, a.k, a.y, a.u_next, kRmsEps, a.slot_planes,
+                       a.slot_plane_stride, a.shared_planes, a.shared_plane_stride);
 }
 
 // Chained stack: u[t] = h[t] / sqrt(mean_j h[t][j]^2 + eps), rounded to the layer dtype.  One workgroup per token;

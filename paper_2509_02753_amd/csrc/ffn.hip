@@ -20,7 +20,10 @@ namespace lexi {
 //   registers as fully coalesced 1 KB wave loads; only the token tile passes through LDS (8 fragment reads per 32 MFMAs).
 //   GATEUP: a wave's blocks 0,1 are gate rows g0..g0+31 and blocks 2,3 the matching up rows, so the epilogue is
 //   silu(gate)*up -> bf16 act[row][f]; the workgroup covers 128 hidden features.
-//   DOWN:   a wave's blocks are 64 consecutive output features; the epilogue stores fp32 out[row][j].
+//   DOWN:   a wave's blocks are 64 consecutive output features; the epilogue stores fp32 out[row][j].  Options: the
+//           reduction cut in two halves handled by two workgroups that write two planes of `out` (more, shorter work
+//           items when a launch would otherwise leave most CUs idle in its last round; the consumer adds the planes);
+//           rows stored at out[scatter[row]] in the caller's dtype (layers with one active expert: no combine pass).
 //   Token rows are gathered through row_token (no permuted copy of X is ever materialised).
 //   Waves whose feature range lies past `features` (ragged last workgroup column) only help staging the tokens.
 // ---------------------------------------------------------------------------------------------------------
@@ -30,13 +33,19 @@ template <bool GATEUP>
 __global__ void __launch_bounds__(256, 2)
 ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_token, const bf16_t* __restrict__ w0,
                 const bf16_t* __restrict__ w1, int K, int features, int M, int tile_tokens,
-                const int32_t* __restrict__ sched, const int32_t* __restrict__ sched_count, void* __restrict__ out) {
+                const int32_t* __restrict__ sched, const int32_t* __restrict__ sched_count, void* __restrict__ out,
+                int ksplit, size_t plane_stride, const int32_t* __restrict__ scatter, int out_bf16) {
     constexpr int TT = 128, TB = TT / 16, WB = 4, KS = BK / 32;
     __shared__ __attribute__((aligned(16))) bf16_t lds_x[2][TT * LDS_LD];
 
     TileInfo ti;
-    int cb;
-    if (!fetch_item(sched, sched_count, (features + (GATEUP ? 127 : 255)) / (GATEUP ? 128 : 256), M, tile_tokens, ti, cb)) return;
+    int cb, part = 0;
+    if (!fetch_item(sched, sched_count, (features + (GATEUP ? 127 : 255)) / (GATEUP ? 128 : 256), M, tile_tokens, ti, cb,
+                    GATEUP ? 1 : ksplit, &part))
+        return;
+    // DOWN with a split reduction: this workgroup covers K-steps [part * nk, (part + 1) * nk) and writes plane `part`
+    const int nk = GATEUP ? K / BK : K / BK / ksplit;
+    const uint32_t kstep0 = GATEUP ? 0u : (uint32_t)(part * nk);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -62,7 +71,8 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
             row = wave_f0 + 16 * fb;
         }
         row = active ? row : 0;
-        abase[fb] = (const char*)(base + ((size_t)ti.expert * (features >> 4) + (row >> 4)) * ((size_t)K * 16));
+        abase[fb] = (const char*)(base + ((size_t)ti.expert * (features >> 4) + (row >> 4)) * ((size_t)K * 16)) +
+                    (size_t)kstep0 * (KS * 1024);
     }
     const uint32_t alane = lane * 16;
 
@@ -74,7 +84,7 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
         const int r = (tid >> 3) + 32 * p;
         const int rr = min(r, ti.rows - 1);  // rows past the group end re-read its last row; never stored
         const int src_row = row_token ? row_token[ti.row0 + rr] : ti.row0 + rr;
-        xoff[p] = (uint32_t)(((size_t)src_row * K + chunk * 8) * 2);
+        xoff[p] = (uint32_t)(((size_t)src_row * K + (size_t)kstep0 * BK + chunk * 8) * 2);
     }
     u32x4_t xreg[4];
     auto load_x = [&](int kt) {
@@ -96,7 +106,6 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
             for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.0f;
 
     bf16x8_t areg[WB][KS];
-    const int nk = K / BK;
     load_x(0);
 #pragma unroll
     for (int fb = 0; fb < WB; ++fb)
@@ -181,11 +190,33 @@ ffn_mfma_kernel(const bf16_t* __restrict__ in, const int32_t* __restrict__ row_t
     } else {
         // (a register transpose to 64-byte runs per lane was measured slower than these 16-byte pieces, which L2 merges)
         if (!active) return;
+        if (scatter != nullptr) {
+            // one active expert per token (gate exactly 1): the row is the layer's output row of its token
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                const int r = tb * 16 + l16;
+                if (r >= ti.rows) continue;
+                const size_t o = (size_t)scatter[ti.row0 + r] * features + wave_f0 + kq * 4;
+#pragma unroll
+                for (int fb = 0; fb < WB; ++fb) {
+                    if (out_bf16) {
+                        u32x2_t pk;
+                        pk[0] = pack_bf16x2(acc[fb][tb][0], acc[fb][tb][1]);
+                        pk[1] = pack_bf16x2(acc[fb][tb][2], acc[fb][tb][3]);
+                        *(u32x2_t*)((bf16_t*)out + o + 16 * fb) = pk;
+                    } else {
+                        *(f32x4_t*)((float*)out + o + 16 * fb) = acc[fb][tb];
+                    }
+                }
+            }
+            return;
+        }
+        float* plane = (float*)out + (size_t)part * plane_stride;
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
             const int r = tb * 16 + l16;
             if (r >= ti.rows) continue;
-            float* o = (float*)out + (size_t)(ti.row0 + r) * features + wave_f0 + kq * 4;
+            float* o = plane + (size_t)(ti.row0 + r) * features + wave_f0 + kq * 4;
 #pragma unroll
             for (int fb = 0; fb < WB; ++fb) *(f32x4_t*)(o + 16 * fb) = acc[fb][tb];
         }
@@ -252,16 +283,20 @@ hipError_t launch_pack(const void* src, void* dst, int64_t n_mat, int R, int K, 
 template <bool GATEUP>
 static hipError_t launch_ffn(const FfnArgs& a, hipStream_t s) {
     if (a.max_tiles <= 0) return hipSuccess;
+    if ((a.ksplit > 1 || a.scatter != nullptr) && !(a.is_bf16 && !a.streaming && !GATEUP))
+        return hipErrorInvalidValue;   // split reduction and scattered rows exist on the bf16 tile schedule's DOWN only
     if (a.is_bf16 && a.streaming) return GATEUP ? launch_gateup_stream(a, s) : launch_down_stream(a, s);
     if (a.is_bf16) {
         // the tile kernel addresses its input rows with 32-bit byte offsets
         const size_t in_rows = a.row_token ? (size_t)a.in_rows : (size_t)a.M;
         if (in_rows * (size_t)a.K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
         const int ncb = (a.features + (GATEUP ? 127 : 255)) / (GATEUP ? 128 : 256);
-        const dim3 grid(xcd_grid(ncb, a.max_tiles));
+        const int ksplit = GATEUP ? 1 : (a.ksplit > 1 ? a.ksplit : 1);
+        if (ksplit > 1 && ((a.K / BK) % ksplit != 0 || a.scatter != nullptr)) return hipErrorInvalidValue;
+        const dim3 grid(xcd_grid(ncb, a.max_tiles, ksplit));
         hipLaunchKernelGGL((ffn_mfma_kernel<GATEUP>), grid, dim3(256), 0, s, (const bf16_t*)a.in, a.row_token,
                            (const bf16_t*)a.w0, (const bf16_t*)a.w1, a.K, a.features, a.M, a.tile_tokens, a.sched,
-                           a.sched_count, a.out);
+                           a.sched_count, a.out, ksplit, a.plane_stride, GATEUP ? nullptr : a.scatter, a.out_bf16 ? 1 : 0);
     } else {
         const dim3 grid((a.features + 255) / 256, a.max_tiles);
         hipLaunchKernelGGL((ffn_f32_kernel<GATEUP>), grid, dim3(256), 0, s, (const float*)a.in, a.row_token,

@@ -55,19 +55,23 @@ __device__ __forceinline__ bool fetch_tile(const int32_t* sched, const int32_t* 
 // The grid is 1-D: 8 * ceil(ncb * max_tiles / 8) workgroups.
 constexpr int kXcds = 8;
 constexpr int kCbGroup = 2;
-inline unsigned xcd_grid(int ncb, int max_tiles) {
-    const long long total = (long long)ncb * max_tiles;
+inline unsigned xcd_grid(int ncb, int max_tiles, int ksplit = 1) {
+    const long long total = (long long)ncb * max_tiles * ksplit;
     return (unsigned)(((total + kXcds - 1) / kXcds) * kXcds);
 }
 
+// With ksplit > 1 every item appears ksplit times in a row, once per part of the reduction dimension.
 __device__ __forceinline__ bool fetch_item(const int32_t* sched, const int32_t* sched_count, int ncb, int M,
-                                           int tile_tokens, TileInfo& ti, int& cb) {
+                                           int tile_tokens, TileInfo& ti, int& cb, int ksplit = 1, int* part = nullptr) {
     const int ntiles = sched != nullptr ? sched_count[0] : (M + tile_tokens - 1) / tile_tokens;
     const int total = ntiles * ncb;
-    const int per = (total + kXcds - 1) / kXcds;
+    const int pieces = total * ksplit;
+    const int per = (pieces + kXcds - 1) / kXcds;
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
-    const int item = xcd * per + slot;
-    if (slot >= per || item >= total) return false;
+    const int piece = xcd * per + slot;
+    if (slot >= per || piece >= pieces) return false;
+    const int item = piece / ksplit;
+    if (part != nullptr) *part = piece - item * ksplit;
     // an expert with n tiles owns n * ncb consecutive items, so tile (item / ncb) belongs to the item's expert
     int first = 0, n = ntiles, erow0 = 0, erows = M;
     ti.expert = 0;

@@ -49,6 +49,11 @@ struct FfnArgs {
     const int32_t* sched;      // null = dense
     const int32_t* sched_count;
     void* out;                 // GATE/UP: act [rows][F] (layer dtype);  DOWN: [rows][d] fp32
+    // DOWN on the tile schedule only:
+    int ksplit;                // 1, or 2: the reduction is cut in two halves, half h writes plane h of `out`
+    size_t plane_stride;       // elements between the planes of `out`
+    const int32_t* scatter;    // null, or row -> output row: rows are stored at out[scatter[row]] (ksplit must be 1)
+    bool out_bf16;             // with scatter: `out` is bf16 (nearest-even rounding of the fp32 result) instead of fp32
 };
 
 hipError_t launch_gateup(const FfnArgs& a, hipStream_t s);
@@ -58,10 +63,15 @@ hipError_t launch_down(const FfnArgs& a, hipStream_t s);
 hipError_t launch_pack(const void* src, void* dst, int64_t n_mat, int R, int K, bool is_bf16, hipStream_t s);
 
 struct CombineArgs {
-    const float* y_slot;       // [T*k][d] fp32, permuted rows
+    const float* y_slot;       // [T*k][d] fp32, permuted rows; `slot_planes` planes, `slot_plane_stride` elements apart,
+                               // that are added (plane order) before the gate is applied
+    int slot_planes;
+    size_t slot_plane_stride;
     const int32_t* inv_perm;   // [T*k]
     const float* gates;        // [T*k]
-    const float* y_shared;     // [T][d] fp32 or null
+    const float* y_shared;     // [T][d] fp32 or null; `shared_planes` planes likewise
+    int shared_planes;
+    size_t shared_plane_stride;
     const void* x;             // [T][d] layer input (only read for a sigmoid-gated shared expert)
     const void* w_shared_gate; // [d] or null (ungated: coefficient 1)
     bool x_bf16;

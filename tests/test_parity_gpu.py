@@ -299,3 +299,26 @@ def test_a_nan_activation_is_routed_safely():
         assert np.isnan(yg[bad]).all()
         keep = np.arange(T) != bad
         assert np.isfinite(yg[keep]).all() and rel_err(yg[keep], ref.out[keep]) <= TOL_BF16
+
+
+@pytest.mark.parametrize("name,d,F,F_shared,T,k,want_routed,want_shared", [
+    ("c2_olmoe", 1024, 2048, 0, 1300, 2, 2, None),      # routed down GEMM on the tile schedule, reduction cut in two
+    ("c2_olmoe", 1024, 2048, 0, 2600, 1, 3, None),      # one active expert: output rows stored by the down GEMM itself
+    ("c2_olmoe", 1024, 1024, 0, 1300, 2, 1, None),      # same sizes, reduction too short to cut: one plane
+    ("c3_qwen15", 1024, 384, 2048, 700, 3, 1, 2),       # shared expert's dense down GEMM cut in two
+    ("c4_mixtral", 1024, 2048, 0, 3700, 2, 2, None),    # few experts, many rows each
+])
+def test_down_gemm_schedules(name, d, F, F_shared, T, k, want_routed, want_shared):
+    """The down GEMM's launch variants at sizes where the tile schedule runs: split reduction (two partial planes added
+    by the combine), direct output rows for k = 1, and the shared expert's split; outputs of sampled tokens against the
+    oracle, routing of every token, and the bf16 output as the rounding of the fp32 output."""
+    import paper_2509_02753_amd as P
+    cfg = S.mini(S.CONFIGS[name], L=1, d=d, F=F, F_shared=F_shared)
+    dl, _ = device_and_host_layer(cfg, 0)
+    assert P.lexi_moe_down_plan(dl, T, k) == want_routed
+    if want_shared is not None:
+        assert P.lexi_moe_down_plan(dl, T, k, shared=True) == want_shared
+    del dl
+    rng = np.random.default_rng(T + k)
+    tokens = np.unique(np.concatenate([[0, T - 1, T // 2], rng.integers(0, T, 93)])).astype(np.int32)
+    run_and_check_layer(cfg, 0, T, k, tokens=tokens)
