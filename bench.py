@@ -369,7 +369,7 @@ def measure_regime(args, mods, cfg, layers, arr, T, cpu_seconds, extras):
     # ---- CPU baseline: the oracle as it stands on a bounded sample of the same workload, timed, and its results
     #      compared with what the GPU produced for the same tokens (routing mismatches, output error)
     cpu, parity = None, None
-    if not args.no_cpu_baseline and cpu_seconds > 0:
+    if not args.no_cpu_baseline and cpu_seconds > 0 and args.operands == "normal":
         import oracle as O
         n = args.cpu_sample_tokens
         # the sample: the first n tokens of the inputs of `nl` layers spread over the stack; n from a pilot so that the
@@ -481,6 +481,11 @@ def main():
     ap.add_argument("--sweep", default=None, choices=["pruning", "budgets"],
                     help="instead of the benchmark line: tokens/s vs active experts for the baseline and the pruned shapes "
                          "(pruning), or tokens/s of per-layer k vectors at every budget B = L*k, k = k_min..k_base (budgets)")
+    ap.add_argument("--operands", default="normal", choices=["normal", "zero-weights"],
+                    help="zero-weights: every expert weight is zero while router and activations stay as they are, so the "
+                         "routing, the tiles and the bytes moved are the same but the matrix cores multiply by zero.  A probe of "
+                         "how far the GEMM rates depend on the operand values (the chip lowers its clock when the multiplier "
+                         "inputs toggle); NOT a valid benchmark result")
     ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
                     help="replay the stack call from a captured HIP graph (auto: for decode-sized batches, whose steps are launch-bound)")
     args = ap.parse_args()
@@ -518,6 +523,10 @@ def main():
         layers = []
         for l in range(L):
             row_major = S.device_layer(cfg, l, dev)          # seeded generator, straight into HBM
+            if args.operands == "zero-weights":
+                for name in ("w_gate", "w_up", "w_down", "ws_gate", "ws_up", "ws_down"):
+                    if row_major.get(name) is not None:
+                        row_major[name].zero_()
             layers.append(P.Layer.from_tensors(row_major, shared_kind=cfg.shared_kind))   # packed by the library's kernel
             del row_major
         torch.cuda.synchronize()
@@ -543,7 +552,8 @@ def main():
 
     h = next(r for r in regimes if (r["name"], r["T"]) == headline)
     out = {
-        "metric": "MoE-stack tokens/s", "value": h["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+        "metric": "MoE-stack tokens/s" if args.operands == "normal" else "MoE-stack tokens/s (operand-value probe, not a valid result)",
+        "operands": args.operands, "value": h["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": h["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": S.CONFIGS[h["name"]].dtype, "data": "synthetic",
         "config": {"workload": h["workload"], "k_vec": h["k_vec"], "k_sum": h["k_sum"], "k_uniform": h["k_uniform"],
