@@ -103,6 +103,34 @@ def test_static_scratch_entry_point_validates_before_launching():
     assert call(fake_layer(P, d=2048, F=1024, E=64), T=4096, k=8) == -5       # 353 MB of workspace
 
 
+def test_down_gemm_plan_is_host_logic():
+    """lexi_moe_down_plan only reads the layer's sizes: the schedule of every case the GPU schedule test runs, and of
+    the full-size workloads, checked here without a GPU (0 streaming, 1 tiles, 2 split reduction, 3 direct rows)."""
+    import paper_2509_02753_amd as P
+    from paper_2509_02753_amd.binding import _lib
+    shared = dict(ws_gate=0x80000, ws_up=0x90000, ws_down=0xA0000, w_shared_gate=0xB0000)
+
+    def plan(T, k, which=0, **kw):
+        ly = fake_layer(P, dtype=1, **kw)
+        return _lib.lexi_moe_down_plan(ctypes.byref(ly), T, k, which)
+
+    assert plan(1300, 2, d=1024, E=64, F=2048) == 2
+    assert plan(2600, 1, d=1024, E=64, F=2048) == 3
+    assert plan(1300, 2, d=1024, E=64, F=1024) == 1
+    assert plan(700, 3, d=1024, E=60, F=384, F_shared=2048, shared_kind=2, **shared) == 1
+    assert plan(700, 3, 1, d=1024, E=60, F=384, F_shared=2048, shared_kind=2, **shared) == 2
+    assert plan(3700, 2, d=1024, E=8, F=4096) == 2
+    # full sizes: prefill runs plain tiles (several rounds of work items), decode streams the weights
+    assert plan(4096, 2, d=4096, E=8, F=14336) == 1 and plan(32, 2, d=4096, E=8, F=14336) == 0
+    assert plan(4096, 8, d=2048, E=64, F=1024) == 1 and plan(4096, 1, d=2048, E=64, F=1024) == 3
+    assert plan(8192, 4, 1, d=2048, E=60, F=1408, F_shared=5632, shared_kind=2, **shared) == 1
+    assert plan(64, 4, 1, d=2048, E=60, F=1408, F_shared=5632, shared_kind=2, **shared) == 0
+    # a k = 1 layer with a shared expert still needs the combine
+    assert plan(2600, 1, d=1024, E=60, F=2048, F_shared=2048, shared_kind=2, **shared) != 3
+    assert plan(16, 1, 1, d=1024, E=8, F=2048) == -1 and plan(0, 1, d=1024, E=8, F=2048) == -1
+    assert plan(16, 9, d=1024, E=8, F=2048) == -1
+
+
 def test_workspace_query_is_monotone_and_checked():
     import paper_2509_02753_amd as P
     from paper_2509_02753_amd.binding import _lib, lexi_layer_t

@@ -306,7 +306,7 @@ def test_a_nan_activation_is_routed_safely():
     ("c2_olmoe", 1024, 2048, 0, 2600, 1, 3, None),      # one active expert: output rows stored by the down GEMM itself
     ("c2_olmoe", 1024, 1024, 0, 1300, 2, 1, None),      # same sizes, reduction too short to cut: one plane
     ("c3_qwen15", 1024, 384, 2048, 700, 3, 1, 2),       # shared expert's dense down GEMM cut in two
-    ("c4_mixtral", 1024, 2048, 0, 3700, 2, 2, None),    # few experts, many rows each
+    ("c4_mixtral", 1024, 4096, 0, 3700, 2, 2, None),    # few experts, many rows each
 ])
 def test_down_gemm_schedules(name, d, F, F_shared, T, k, want_routed, want_shared):
     """The down GEMM's launch variants at sizes where the tile schedule runs: split reduction (two partial planes added
