@@ -343,7 +343,11 @@ def measure_regime(args, mods, cfg, layers, arr, T, cpu_seconds, extras):
                     for l in range(L))
     gu_ms, dn_ms = float(stage_ms[:, 1].mean()), float(stage_ms[:, 2].mean())
     gu_kernel = "ffn_mfma_kernel<gate_up>" if prefill else "ffn_mfma_kernel<gate_up> / ffn_stream_kernel<gate_up> (by rows per expert)"
-    dn_kernel = "ffn_mfma_kernel<down>" if prefill else "ffn_mfma_kernel<down> / ffn_stream_kernel<down> (by work items)"
+    plan_names = {0: "ffn_stream_kernel<down>", 1: "ffn_mfma_kernel<down>", 2: "ffn_mfma_kernel<down> (reduction cut in two)",
+                  3: "ffn_mfma_kernel<down> (output rows stored directly, no combine launch)",
+                  4: "down_combine_kernel (down projection and combine in one launch; its stage time includes the wait "
+                     "for the shared expert's side stream)"}
+    dn_kernel = " / ".join(plan_names[p] for p in sorted({P.lexi_moe_down_plan(layers[l], T, int(kvec[l])) for l in range(L)}))
     roof_gu = kernel_roofline("gate_up", gu_kernel, prefill, sum(gu_flops) / L, sum(gu_bytes) / L, gu_ms,
                               stored_traffic(cfg.name, T))
     roof_dn = kernel_roofline("down", dn_kernel, prefill, sum(dn_flops) / L, sum(dn_bytes) / L, dn_ms)

@@ -21,7 +21,8 @@ lexi_status lexi_probe_hbm_read(const void* src, size_t bytes, void* sink, void*
  *   which = 0: the routed experts' down GEMM; which = 1: the shared expert's.
  *   Returns 0 = weight-streaming schedule (decode-sized), 1 = tile schedule, 2 = tile schedule with the reduction cut
  *   in two (two partial planes, added by the combine), 3 = tile schedule storing the output rows directly (k = 1 and
- *   nothing else to add: no combine pass); -1 = invalid arguments or no shared expert. */
+ *   nothing else to add: no combine pass), 4 = a handful of tokens: weight streaming with the combine in the same
+ *   launch; -1 = invalid arguments or no shared expert. */
 int32_t lexi_moe_down_plan(const lexi_layer_t* layer, int32_t T, int32_t k, int32_t which);
 
 #ifdef __cplusplus

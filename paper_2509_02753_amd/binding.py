@@ -315,7 +315,8 @@ def lexi_allocate_topk(D, B: int, k_min: int, k_max: int, n_pop: int = 32, g_max
 
 def lexi_moe_down_plan(layer: Layer, T: int, k: int, shared: bool = False) -> int:
     """Schedule of the (routed or shared) down GEMM of a call: 0 streaming, 1 tiles, 2 tiles with the reduction cut in
-    two, 3 tiles storing the output rows directly; -1 if there is no such GEMM."""
+    two, 3 tiles storing the output rows directly, 4 streaming with the combine in the same launch; -1 if there is no
+    such GEMM."""
     return int(_lib.lexi_moe_down_plan(ctypes.byref(layer.c), int(T), int(k), 1 if shared else 0))
 
 

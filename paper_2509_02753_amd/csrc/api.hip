@@ -206,6 +206,7 @@ struct DownPlan {
     bool routed_streams, shared_streams;   // weight-streaming schedule instead of the tile schedule
     int routed_ksplit, shared_ksplit;      // parts of the reduction on the tile schedule (1 or 2)
     bool routed_direct;                    // with k == 1 and nothing to add: rows stored straight into y
+    bool routed_fused;                     // a handful of tokens: down projection and combine in one launch
 };
 DownPlan plan_down(const lexi_layer_t& ly, int32_t T, int32_t k, bool allow_split, bool allow_direct) {
     DownPlan p{};
@@ -220,6 +221,9 @@ DownPlan plan_down(const lexi_layer_t& ly, int32_t T, int32_t k, bool allow_spli
     p.routed_ksplit = p.shared_ksplit = 1;
     const bool tile_routed = bf && !p.routed_streams;
     p.routed_direct = tile_routed && allow_direct && k == 1 && ly.F_shared == 0;
+    // (allow_direct: the caller wants nothing but y -- no slot rows, no residual, no normalised copy)
+    p.routed_fused = bf && p.routed_streams && allow_direct && T <= kFusedDownMaxT && A <= kFusedDownMaxRows &&
+                     ly.shared_kind != LEXI_SHARED_SIGMOID;
     if (tile_routed && allow_split && !p.routed_direct) p.routed_ksplit = choose_ksplit(A, ly.E, ly.F, ly.d, bf);
     if (ly.F_shared > 0 && bf && !p.shared_streams) p.shared_ksplit = choose_ksplit(T, 1, ly.F_shared, ly.d, bf);
     return p;
@@ -227,7 +231,7 @@ DownPlan plan_down(const lexi_layer_t& ly, int32_t T, int32_t k, bool allow_spli
 
 lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t k, Workspace& w, hipStream_t s,
                        const lexi_stage_events_t* events, bool allow_split = true, void* direct_y = nullptr,
-                       bool direct_bf16 = false) {
+                       bool direct_bf16 = false, hipEvent_t shared_done = nullptr) {
     auto mark = [&](int i) {
         if (events && events->ev[i]) (void)hipEventRecord((hipEvent_t)events->ev[i], s);
     };
@@ -259,7 +263,18 @@ lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t
     dn.streaming = plan.routed_streams;
     dn.ksplit = w.slot_planes = plan.routed_ksplit;
     dn.plane_stride = (size_t)T * k * ly.d;
-    w.direct = plan.routed_direct;
+    w.direct = plan.routed_direct || plan.routed_fused;
+    if (plan.routed_fused) {
+        // the fused kernel adds the shared expert's rows: they must be complete before it starts
+        if (shared_done != nullptr && hipStreamWaitEvent(s, shared_done, 0) != hipSuccess) return LEXI_ERR_LAUNCH;
+        DownCombineArgs f{};
+        f.act = w.act; f.w_down = ly.w_down; f.F = ly.F; f.d = ly.d; f.T = T; f.k = k; f.sched = w.sched;
+        f.sched_count = w.sched_count; f.inv_perm = w.inv_perm; f.gates = w.gates;
+        f.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr; f.y = direct_y; f.y_bf16 = direct_bf16;
+        if (launch_down_combine(f, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+        mark(3);
+        return LEXI_OK;
+    }
     if (plan.routed_direct) {
         dn.out = direct_y; dn.scatter = w.row_token; dn.out_bf16 = direct_bf16;
     }
@@ -327,14 +342,19 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
         if (hipEventRecord(side->join, side->stream) != hipSuccess) return LEXI_ERR_LAUNCH;
     }
 
+    // Nothing but y to produce (no residual, no normalised copy): the routed down launch may write y itself -- with
+    // one active expert and no shared one on the tile schedule, or for a handful of tokens with the combine fused in
+    // (plan_down decides).  The fused launch consumes the shared expert's rows, so those come first then.
+    const bool direct = hidden == nullptr && u_out == nullptr;
+    const bool fused = plan_down(ly, T, k, true, direct).routed_fused;
+    if (fused && ly.F_shared > 0 && !side && !run_shared(s)) return LEXI_ERR_LAUNCH;
     {
-        // one active expert, nothing else to add, no normalised copy to produce: the down GEMM can write y itself
-        const bool direct = hidden == nullptr && u_out == nullptr;   // (plan_down adds: k == 1, no shared expert, tile schedule)
-        const lexi_status st = run_routed(ly, x, T, k, w, s, events, true, direct ? y : nullptr, y_dtype == LEXI_BF16);
+        const lexi_status st = run_routed(ly, x, T, k, w, s, events, true, direct ? y : nullptr, y_dtype == LEXI_BF16,
+                                          (fused && side && ly.F_shared > 0) ? side->join : nullptr);
         if (st != LEXI_OK) return st;
     }
 
-    if (ly.F_shared > 0) {
+    if (ly.F_shared > 0 && !fused) {
         if (side) {
             if (hipStreamWaitEvent(s, side->join, 0) != hipSuccess) return LEXI_ERR_LAUNCH;
         } else if (!run_shared(s)) {
@@ -530,7 +550,7 @@ int32_t lexi_moe_down_plan(const lexi_layer_t* layer, int32_t T, int32_t k, int3
     if (check_layer(layer) != LEXI_OK || T < 1 || k < 1 || k > layer->E) return -1;
     const DownPlan p = plan_down(*layer, T, k, true, true);
     switch (which) {
-        case 0: return p.routed_streams ? 0 : (p.routed_direct ? 3 : p.routed_ksplit);
+        case 0: return p.routed_fused ? 4 : (p.routed_streams ? 0 : (p.routed_direct ? 3 : p.routed_ksplit));
         case 1: return layer->F_shared == 0 ? -1 : (p.shared_streams ? 0 : p.shared_ksplit);
         default: return -1;
     }

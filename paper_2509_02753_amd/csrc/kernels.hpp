@@ -83,6 +83,25 @@ struct CombineArgs {
 };
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
 
+// Down projection and combine of a decode-sized batch in one launch (bf16 layers, T <= kFusedDownMaxT, T*k <=
+// kFusedDownMaxRows, shared expert absent or ungated): y[t] = sum_s gates[t][s] * (act[row(t, s)] . W_down[e]) in slot
+// order, then the shared expert's row.
+constexpr int kFusedDownMaxT = 8;      // beyond these the separate launches measured faster (more experts with rows than
+constexpr int kFusedDownMaxRows = 64;  // the d/16 workgroups of the fused launch can stream at full rate)
+struct DownCombineArgs {
+    const void* act;           // [T*k][F] bf16, permuted rows
+    const void* w_down;        // [E] packed matrices of [d][F]
+    int F, d, T, k;
+    const int32_t* sched;      // tile schedule (one tile per expert with rows)
+    const int32_t* sched_count;
+    const int32_t* inv_perm;   // [T*k]
+    const float* gates;        // [T*k]
+    const float* y_shared;     // [T][d] fp32 or null (added with coefficient 1)
+    void* y;                   // [T][d]
+    bool y_bf16;
+};
+hipError_t launch_down_combine(const DownCombineArgs& a, hipStream_t s);
+
 // chained stack: normalised MoE input u (layer dtype) from the fp32 hidden state h; h = widened x
 constexpr float kRmsEps = 1e-6f;
 hipError_t launch_rmsnorm(const float* h, int T, int d, float eps, void* u, bool u_bf16, hipStream_t s);

@@ -122,6 +122,13 @@ def test_down_gemm_plan_is_host_logic():
     assert plan(3700, 2, d=1024, E=8, F=4096) == 2
     # full sizes: prefill runs plain tiles (several rounds of work items), decode streams the weights
     assert plan(4096, 2, d=4096, E=8, F=14336) == 1 and plan(32, 2, d=4096, E=8, F=14336) == 0
+    # a handful of tokens (T <= 8, T*k <= 64, no sigmoid-gated shared expert): the combine rides in the down launch
+    assert plan(1, 6, d=2048, E=64, F=1408, F_shared=2816, shared_kind=1, ws_gate=0x80000, ws_up=0x90000,
+                ws_down=0xA0000) == 4
+    assert plan(8, 2, d=4096, E=8, F=14336) == 4 and plan(9, 2, d=4096, E=8, F=14336) == 0
+    assert plan(8, 8, d=2048, E=64, F=1024) == 4 and plan(8, 9, d=2048, E=64, F=1024) == 0
+    assert plan(16, 16, d=2048, E=64, F=1024) == 1     # enough work items for the tile schedule: not fused
+    assert plan(4, 4, d=2048, E=60, F=1408, F_shared=5632, shared_kind=2, **shared) == 0
     assert plan(4096, 8, d=2048, E=64, F=1024) == 1 and plan(4096, 1, d=2048, E=64, F=1024) == 3
     assert plan(8192, 4, 1, d=2048, E=60, F=1408, F_shared=5632, shared_kind=2, **shared) == 1
     assert plan(64, 4, 1, d=2048, E=60, F=1408, F_shared=5632, shared_kind=2, **shared) == 0

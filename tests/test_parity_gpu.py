@@ -322,3 +322,25 @@ def test_down_gemm_schedules(name, d, F, F_shared, T, k, want_routed, want_share
     rng = np.random.default_rng(T + k)
     tokens = np.unique(np.concatenate([[0, T - 1, T // 2], rng.integers(0, T, 93)])).astype(np.int32)
     run_and_check_layer(cfg, 0, T, k, tokens=tokens)
+
+
+@pytest.mark.parametrize("name,T,k,want", [
+    ("c4_mixtral", 1, 1, 4),     # one expert with rows: its reduction is dealt out over all sixteen waves
+    ("c4_mixtral", 1, 2, 4),     # two experts
+    ("c2_olmoe", 1, 3, 4), ("c2_olmoe", 2, 4, 4), ("c2_olmoe", 3, 5, 4),   # 3, up to 8, nine or more experts per pass
+    ("c5_dsv2lite", 8, 6, 4),    # more experts than one pass holds, ungated shared expert added in the same launch
+    ("c2_olmoe", 8, 8, 4),       # the most tokens and rows the fused launch takes (slots beyond the prefetched eight: none)
+    ("c2_olmoe", 4, 16, 4),      # sixteen slots per token: the second half of the slots is fetched in the combine loop
+    ("c2_olmoe", 8, 9, 0),       # one row too many: separate down and combine launches
+    ("c5_dsv2lite", 9, 2, 0),    # one token too many
+    ("c3_qwen15", 4, 4, 0),      # sigmoid-gated shared expert: its coefficient is evaluated by the combine kernel
+])
+def test_down_projection_with_the_combine_fused_for_a_handful_of_tokens(name, T, k, want):
+    """Decode-sized calls: the routed down projection forms y itself (plan value 4) -- every way of dealing the waves
+    out over the experts, several passes, the shared expert's rows -- and the sizes just outside that path."""
+    import paper_2509_02753_amd as P
+    cfg = S.mini(S.CONFIGS[name], L=1, d=256, F=448)     # 14 K-blocks of 32: not divisible by 4, 8 or 16 waves
+    dl, _ = device_and_host_layer(cfg, 0)
+    assert P.lexi_moe_down_plan(dl, T, k) == want
+    del dl
+    run_and_check_layer(cfg, 0, T, k)
