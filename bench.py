@@ -345,8 +345,7 @@ def measure_regime(args, mods, cfg, layers, arr, T, cpu_seconds, extras):
     gu_kernel = "ffn_mfma_kernel<gate_up>" if prefill else "ffn_mfma_kernel<gate_up> / ffn_stream_kernel<gate_up> (by rows per expert)"
     plan_names = {0: "ffn_stream_kernel<down>", 1: "ffn_mfma_kernel<down>", 2: "ffn_mfma_kernel<down> (reduction cut in two)",
                   3: "ffn_mfma_kernel<down> (output rows stored directly, no combine launch)",
-                  4: "down_combine_kernel (down projection and combine in one launch; its stage time includes the wait "
-                     "for the shared expert's side stream)"}
+                  4: "down_combine_kernel (down projection and combine in one launch)"}
     dn_kernel = " / ".join(plan_names[p] for p in sorted({P.lexi_moe_down_plan(layers[l], T, int(kvec[l])) for l in range(L)}))
     roof_gu = kernel_roofline("gate_up", gu_kernel, prefill, sum(gu_flops) / L, sum(gu_bytes) / L, gu_ms,
                               stored_traffic(cfg.name, T))

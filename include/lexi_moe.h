@@ -161,7 +161,9 @@ lexi_status lexi_moe_stack_forward(const lexi_layer_t* layers, int32_t L, const 
 /* Stage boundaries of one layer, for timing from outside with HIP events: the library records ev[i] on the
  * stream at boundary i.  0 = layer start, 1 = routing done (router, top-k, gates, permutation), 2 = routed gate/up
  * GEMM + SwiGLU done, 3 = routed down GEMM done, 4 = shared expert done, 5 = combine done.  A NULL event is
- * skipped.  Events are hipEvent_t handles owned by the caller (host struct). */
+ * skipped.  Events are hipEvent_t handles owned by the caller (host struct).  A call for a handful of tokens whose
+ * down projection and combine are one launch (it consumes the shared expert's rows) records 4 BEFORE that launch and
+ * 3 and 5 after it. */
 #define LEXI_N_STAGE_EVENTS 6
 typedef struct {
     void* ev[LEXI_N_STAGE_EVENTS];

@@ -354,5 +354,14 @@ class StageEvents:
                 self.c[l].ev[i] = e.cuda_event
 
     def stage_ms(self):
-        """After a synchronize: per-layer list of the 5 stage durations in milliseconds."""
-        return [[row[i].elapsed_time(row[i + 1]) for i in range(N_STAGE_EVENTS - 1)] for row in self.events]
+        """After a synchronize: per-layer list of the 5 stage durations in milliseconds (routing, gate/up, down, shared,
+        combine).  Where the library recorded "shared expert done" before "down done" (down projection and combine in
+        one launch), the wait for the shared expert is the shared stage and the launch is the down stage."""
+        out = []
+        for row in self.events:
+            t = [row[0].elapsed_time(e) for e in row]
+            if t[4] < t[3]:
+                out.append([t[1], t[2] - t[1], t[3] - t[4], t[4] - t[2], t[5] - t[3]])
+            else:
+                out.append([t[i + 1] - t[i] for i in range(N_STAGE_EVENTS - 1)])
+        return out

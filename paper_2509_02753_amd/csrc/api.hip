@@ -107,6 +107,7 @@ struct Workspace {
     int max_tiles;
     int slot_planes = 1, shared_planes = 1;   // planes of y_slot / y_shared the last launches wrote
     bool direct = false;                      // the routed down GEMM wrote the layer's output itself
+    bool fused = false;                       // the caller launches down + combine as one kernel (run_routed stopped after gate/up)
     size_t bytes;
 };
 
@@ -231,7 +232,7 @@ DownPlan plan_down(const lexi_layer_t& ly, int32_t T, int32_t k, bool allow_spli
 
 lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t k, Workspace& w, hipStream_t s,
                        const lexi_stage_events_t* events, bool allow_split = true, void* direct_y = nullptr,
-                       bool direct_bf16 = false, hipEvent_t shared_done = nullptr) {
+                       bool direct_bf16 = false) {
     auto mark = [&](int i) {
         if (events && events->ev[i]) (void)hipEventRecord((hipEvent_t)events->ev[i], s);
     };
@@ -263,18 +264,9 @@ lexi_status run_routed(const lexi_layer_t& ly, const void* x, int32_t T, int32_t
     dn.streaming = plan.routed_streams;
     dn.ksplit = w.slot_planes = plan.routed_ksplit;
     dn.plane_stride = (size_t)T * k * ly.d;
-    w.direct = plan.routed_direct || plan.routed_fused;
-    if (plan.routed_fused) {
-        // the fused kernel adds the shared expert's rows: they must be complete before it starts
-        if (shared_done != nullptr && hipStreamWaitEvent(s, shared_done, 0) != hipSuccess) return LEXI_ERR_LAUNCH;
-        DownCombineArgs f{};
-        f.act = w.act; f.w_down = ly.w_down; f.F = ly.F; f.d = ly.d; f.T = T; f.k = k; f.sched = w.sched;
-        f.sched_count = w.sched_count; f.inv_perm = w.inv_perm; f.gates = w.gates;
-        f.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr; f.y = direct_y; f.y_bf16 = direct_bf16;
-        if (launch_down_combine(f, s) != hipSuccess) return LEXI_ERR_LAUNCH;
-        mark(3);
-        return LEXI_OK;
-    }
+    w.direct = plan.routed_direct;
+    w.fused = plan.routed_fused;
+    if (plan.routed_fused) return LEXI_OK;   // run_layer launches down + combine once the shared expert's rows are there
     if (plan.routed_direct) {
         dn.out = direct_y; dn.scatter = w.row_token; dn.out_bf16 = direct_bf16;
     }
@@ -344,17 +336,36 @@ lexi_status run_layer(const lexi_layer_t& ly, const void* x, void* y, int32_t y_
 
     // Nothing but y to produce (no residual, no normalised copy): the routed down launch may write y itself -- with
     // one active expert and no shared one on the tile schedule, or for a handful of tokens with the combine fused in
-    // (plan_down decides).  The fused launch consumes the shared expert's rows, so those come first then.
+    // (plan_down decides).
     const bool direct = hidden == nullptr && u_out == nullptr;
-    const bool fused = plan_down(ly, T, k, true, direct).routed_fused;
-    if (fused && ly.F_shared > 0 && !side && !run_shared(s)) return LEXI_ERR_LAUNCH;
     {
-        const lexi_status st = run_routed(ly, x, T, k, w, s, events, true, direct ? y : nullptr, y_dtype == LEXI_BF16,
-                                          (fused && side && ly.F_shared > 0) ? side->join : nullptr);
+        const lexi_status st = run_routed(ly, x, T, k, w, s, events, true, direct ? y : nullptr, y_dtype == LEXI_BF16);
         if (st != LEXI_OK) return st;
     }
+    const bool fused = w.fused;
+    if (fused) {
+        // the fused launch consumes the shared expert's rows, so the join (or the in-line shared expert) comes first;
+        // the stage events keep their meaning: 4 = shared expert done, 3 = routed down done (= 5, combine done)
+        if (ly.F_shared > 0) {
+            if (side) {
+                if (hipStreamWaitEvent(s, side->join, 0) != hipSuccess) return LEXI_ERR_LAUNCH;
+            } else if (!run_shared(s)) {
+                return LEXI_ERR_LAUNCH;
+            }
+            mark(4);
+        }
+        DownCombineArgs f{};
+        f.act = w.act; f.w_down = ly.w_down; f.F = ly.F; f.d = ly.d; f.T = T; f.k = k; f.sched = w.sched;
+        f.sched_count = w.sched_count; f.inv_perm = w.inv_perm; f.gates = w.gates;
+        f.y_shared = ly.F_shared > 0 ? w.y_shared : nullptr; f.y = y; f.y_bf16 = y_dtype == LEXI_BF16;
+        if (launch_down_combine(f, s) != hipSuccess) return LEXI_ERR_LAUNCH;
+        mark(3);
+        if (ly.F_shared == 0) mark(4);
+        mark(5);
+        return LEXI_OK;
+    }
 
-    if (ly.F_shared > 0 && !fused) {
+    if (ly.F_shared > 0) {
         if (side) {
             if (hipStreamWaitEvent(s, side->join, 0) != hipSuccess) return LEXI_ERR_LAUNCH;
         } else if (!run_shared(s)) {

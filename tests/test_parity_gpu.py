@@ -344,3 +344,28 @@ def test_down_projection_with_the_combine_fused_for_a_handful_of_tokens(name, T,
     assert P.lexi_moe_down_plan(dl, T, k) == want
     del dl
     run_and_check_layer(cfg, 0, T, k)
+
+
+@pytest.mark.parametrize("name,T", [("c5_dsv2lite", 3), ("c5_dsv2lite", 150), ("c2_olmoe", 2), ("c3_qwen15", 5)])
+def test_profiled_stack_records_its_stage_events_and_changes_nothing(name, T):
+    """lexi_moe_stack_forward_profiled: the same bits as the plain stack call, and five stage durations per layer
+    that are non-negative and add up to the layer's span -- also where the shared expert's join is recorded before
+    the launch that holds both the down projection and the combine (T = 2, 3: ungated / no shared expert)."""
+    import torch
+    import paper_2509_02753_amd as P
+    cfg = S.mini(S.CONFIGS[name], L=3, d=256, F=384)
+    kv = cfg.k_lexi()
+    dls = [device_and_host_layer(cfg, l)[0] for l in range(cfg.L)]
+    x = torch.stack([S.device_x(cfg, l, T) for l in range(cfg.L)])
+    y0 = torch.empty((cfg.L, T, cfg.d), dtype=torch.float32, device="cuda:0")
+    y1 = torch.empty_like(y0)
+    ws = P.alloc_workspace(dls, T, int(kv.max()))
+    P.lexi_moe_stack_forward(dls, kv, x, y0, ws)
+    ev = P.StageEvents(cfg.L)
+    P.lexi_moe_stack_forward(dls, kv, x, y1, ws, stage_events=ev)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    for row, st in zip(ev.events, ev.stage_ms()):
+        assert len(st) == 5 and all(v >= 0.0 for v in st)
+        assert abs(sum(st) - row[0].elapsed_time(row[5])) < 1e-3
+        assert st[0] > 0.0 and st[1] > 0.0 and st[2] > 0.0    # routing, gate/up and down always launch something
