@@ -137,13 +137,16 @@ def test_pack_weights_matches_the_documented_index(dtype):
         P.lexi_pack_weights(torch.zeros((40, 96), dtype=torch.bfloat16, device="cuda"))   # rows % 16 != 0
 
 
-def test_stack_replayed_from_a_hip_graph_matches_eager():
+@pytest.mark.parametrize("name,T", [
+    ("c3_qwen15", 40),     # sigmoid-gated shared expert: the side stream is in the capture, joined before the combine
+    ("c5_dsv2lite", 4),    # ungated shared expert, a handful of tokens: joined before the launch that holds down + combine
+])
+def test_stack_replayed_from_a_hip_graph_matches_eager(name, T):
     """A captured stack call (side-stream fork/join of the shared expert included) replays to the eager result,
     every time, with eager work and synchronisations between the replays."""
     import torch
     import paper_2509_02753_amd as P
-    cfg = S.mini(S.C3, L=3, d=256, F=384)   # sigmoid-gated shared expert: the side stream is in the capture
-    T = 40
+    cfg = S.mini(S.CONFIGS[name], L=3, d=256, F=384)
     kv = cfg.k_lexi()
     dls = [device_and_host_layer(cfg, l)[0] for l in range(cfg.L)]
     x = torch.stack([S.device_x(cfg, l, T) for l in range(cfg.L)])
