@@ -372,3 +372,22 @@ def test_profiled_stack_records_its_stage_events_and_changes_nothing(name, T):
         assert len(st) == 5 and all(v >= 0.0 for v in st)
         assert abs(sum(st) - row[0].elapsed_time(row[5])) < 1e-3
         assert st[0] > 0.0 and st[1] > 0.0 and st[2] > 0.0    # routing, gate/up and down always launch something
+
+
+@pytest.mark.parametrize("name,inter,d,T,k", [
+    ("c4_mixtral", 0.0, 256, 1300, 2),     # 8 experts, prefill-sized: packed partials, eight tokens per wave in the top-k
+    ("c4_mixtral", 0.0, 640, 2500, 2),     # five router segments (the second workgroup's last three waves idle), 16-token blocks
+    ("c2_olmoe", 0.75, 256, 2100, 3),      # 16 experts (the shape inter-pruning three quarters of OLMoE's leaves)
+    ("c5_dsv2lite", 0.875, 384, 1100, 4),  # 8 experts with a router bias and a shared expert
+    ("c4_mixtral", 0.0, 256, 1024, 2),     # one token fewer than the narrow kernel's range: the 64-lane partials
+])
+def test_router_partials_for_eight_and_sixteen_experts(name, inter, d, T, k):
+    """Prefill-sized batches on layers with exactly 8 or 16 experts take the narrow partial kernel (lane = token,
+    weights by scalar loads, packed rows of partials): routing bit-exact on every token, outputs on a sample."""
+    cfg = S.mini(S.CONFIGS[name], L=1, d=d, F=256)
+    if inter:
+        cfg = S.pruned(cfg, inter=inter)
+    assert cfg.E in (8, 16)
+    rng = np.random.default_rng(T)
+    tokens = np.unique(np.concatenate([[0, T - 1], rng.integers(0, T, 62)])).astype(np.int32)
+    run_and_check_layer(cfg, 0, T, k, tokens=tokens)
